@@ -1,0 +1,151 @@
+/*
+ * tq.h -- C ABI of the truncated quantizer for heavy-tailed gradients
+ *         (arXiv 2402.01798) on AMD MI355X (gfx950).
+ *
+ * The four calls follow the paper's statement of the problem: a worker designs
+ * the two parameters of its quantizer from the statistics of its gradient
+ * (Sec. IV), sends Q[T_alpha(g)] in b bits per element (Sec. III-A, Alg. 1
+ * client step), and the server averages what the N workers sent (Alg. 1
+ * server step).
+ *
+ * Conventions shared by every call
+ *   - Pointers named *_dev are device (HBM) pointers, 16-byte aligned, owned
+ *     by the caller; the library never allocates, frees or keeps them.
+ *   - Pointers named *_host are host memory, read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued asynchronously; no call synchronises the stream.
+ *   - Return value: TQ_OK or an error code; nothing is enqueued on error.
+ *     A bad argument is TQ_EINVAL, a misaligned pointer TQ_EALIGN, a size the
+ *     kernels do not cover TQ_EUNSUPPORTED, a failed launch TQ_EHIP.
+ *   - d = elements in one worker's flat gradient (d >= 1).  bucket_elems = 0
+ *     means one bucket spanning the tensor; otherwise consecutive buckets of
+ *     bucket_elems elements (a multiple of 128), the last possibly short.
+ *     There is one tq_stats_t and one tq_params_t per bucket.
+ */
+#ifndef TQ_H
+#define TQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { TQ_OK = 0, TQ_EINVAL = 1, TQ_EALIGN = 2, TQ_EUNSUPPORTED = 3, TQ_EHIP = 4 };
+enum { TQ_F32 = 0, TQ_BF16 = 1 };                      /* gradient dtype */
+enum { TQ_GRID_UNIFORM = 0, TQ_GRID_NONUNIFORM = 1 };  /* codebook family */
+
+#define TQ_NBINS 898        /* histogram bins of |g|, see tq_stats */
+#define TQ_MAX_WORKERS 64   /* largest N of tq_decompress_aggregate */
+
+/* tq_params_t.flags */
+#define TQ_F_ALPHA_CLAMPED_MAX 1u  /* fixed point at or beyond max|g|: alpha = max|g| */
+#define TQ_F_GAMMA_CLAMPED     2u  /* tail index estimate below 2.02, lifted to it   */
+#define TQ_F_NOT_CONVERGED     4u  /* 100 iterations without meeting 1e-10           */
+#define TQ_F_DEGENERATE        8u  /* no finite non-zero data, or no usable tail      */
+#define TQ_F_ALPHA_OVERRIDE   16u  /* alpha given by the caller                       */
+#define TQ_F_ALPHA_CLAMPED_MIN 32u /* fixed point at or below g_min, lifted           */
+
+/* Per-bucket statistics of |g| (3632 bytes).  The integer fields are exact. */
+typedef struct {
+    uint32_t hist[TQ_NBINS]; /* bin 0: [0,2^-40); bins 1..896: sixteenths of the octaves
+                                of [2^-40,2^16); bin 897: [2^16,inf).  Finite values only. */
+    uint32_t n_nonfinite;    /* NaN and +-Inf seen (left out of every other field)     */
+    float    absmax;         /* largest finite |g|                                      */
+    uint64_t n;              /* elements in the bucket                                  */
+    float    g_min;          /* the g_min given to tq_stats, 0 if none                  */
+    uint32_t reserved;
+    uint64_t n_tail;         /* #{|g| > g_min}            (g_min > 0 only, else 0)      */
+    double   sum_log_tail;   /* sum of ln(|g|/g_min) over them (g_min > 0 only)         */
+} tq_stats_t;
+
+/* Per-bucket quantizer parameters (160 bytes): what a worker sends beside its codes. */
+typedef struct {
+    float    alpha;          /* truncation threshold, > 0                               */
+    uint32_t bits, s, grid;  /* b, s = 2^b - 1, TQ_GRID_*                               */
+    float    level[16];      /* l_0 = -alpha < ... < l_s = +alpha; rest 0               */
+    float    inv_w[16];      /* (float)(1/(l_{k+1}-l_k)), 0 for an empty cell; uniform
+                                grid: every entry (float)(s/(2 alpha))                  */
+    float    gamma_hat, rho_hat, g_min; /* estimates the design used (0 if none)        */
+    uint32_t flags;          /* TQ_F_*                                                  */
+} tq_params_t;
+
+/* Number of buckets, and bytes of one worker's packed payload: the b-bit codes
+ * form one little-endian bit stream (element e at bits [e*b, e*b+b)), padded
+ * with zero bits to a multiple of 16 bytes.  Pure host arithmetic. */
+uint64_t tq_num_buckets(uint64_t d, uint64_t bucket_elems);
+uint64_t tq_payload_bytes(uint64_t d, int bits);
+
+/*
+ * tq_stats -- the reductions the parameter design consumes (Sec. IV-A: tail
+ * mass rho and Q_U(alpha); Sec. IV-B: integral of p^(1/3); Sec. V: the two
+ * terms of the maximum-likelihood tail index gamma = 1 + n/sum ln(g_j/g_min)).
+ *   g_dev      [d] gradient, TQ_F32 (float) or TQ_BF16 (uint16 bit patterns)
+ *   g_min      > 0: also count and log-sum the elements with |g| > g_min
+ *              (must be >= 2^-40); <= 0: leave the tail to tq_params
+ *   stats_dev  [tq_num_buckets] written in full (zeroed, then reduced into
+ *              with integer atomics; sum_log_tail with fp64 atomics, so its
+ *              last bits depend on the order of arrival)
+ */
+int tq_stats(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
+             float g_min, tq_stats_t* stats_dev, void* stream);
+
+/*
+ * tq_params -- the two parameters of the quantizer, per bucket (Sec. IV):
+ * truncation threshold alpha by the fixed point of the boxed equation of
+ * Sec. IV-A (uniform grid, Q_U) or Sec. IV-B (non-uniform grid, Q_N), and the
+ * codebook: l_k = -alpha + k 2alpha/s, or the levels at which the integral of
+ * lambda_s ~ p^(1/3) (Sec. IV-B, first boxed equation) reaches k.  p inside
+ * [-alpha, alpha] is the histogram's density; gamma, rho come from the tail
+ * terms of tq_stats or, without g_min, from the bins above the 0.9-quantile.
+ *   stats_dev       [nb] from tq_stats
+ *   bits            b in {2,3,4}
+ *   alpha_override  0: the paper's formula; > 0: use this alpha;
+ *                   < 0: alpha = max|g| (quantization without truncation)
+ *   params_dev      [nb] written in full
+ * All arithmetic is fp64 on the device, one workgroup per bucket.
+ */
+int tq_params(const tq_stats_t* stats_dev, uint64_t nb, int bits, int grid,
+              float alpha_override, tq_params_t* params_dev, void* stream);
+
+/*
+ * tq_compress -- Alg. 1 client step: code[e] = Q[T_alpha(g[e])] (Eq. 1, Eq. 2)
+ * on the bucket's codebook, packed to b bits.  The rounding of element e uses
+ * 16 bits of Philox4x32-10 with counter (e >> 3, worker, step) and key `seed`,
+ * so the payload is a pure function of (g, params, seed, worker, step).
+ *   g_dev        [d] gradient (dtype as in tq_stats)
+ *   params_dev   [tq_num_buckets]; all records must carry the same bits
+ *                (read on the device: a mismatch cannot be reported)
+ *   bits         b in {2,3,4}, the bits of params_dev
+ *   payload_dev  [tq_payload_bytes(d, bits)] written in full, padding included
+ */
+int tq_compress(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
+                const tq_params_t* params_dev, int bits, uint64_t seed,
+                uint32_t worker, uint32_t step, void* payload_dev, void* stream);
+
+/*
+ * tq_decompress_aggregate -- Alg. 1 server step: out[e] = sum_i w_i L_i[c_i(e)]
+ * over the N workers' payloads in one pass, in binary32, in worker order.
+ *   payload_host  [N] host array of device pointers to the payloads
+ *   params_host   [N] host array of device pointers to each worker's
+ *                 [tq_num_buckets] parameter records
+ *   weights_host  NULL: w_i = 1/N, applied once to the sum (Lemma 2);
+ *                 else [N] floats, each level is scaled before it is added
+ *   N             1 .. TQ_MAX_WORKERS
+ *   accumulate    0: out = result; 1: out += result
+ *   out_dev       [d] floats
+ */
+int tq_decompress_aggregate(const void* const* payload_host,
+                            const tq_params_t* const* params_host,
+                            const float* weights_host, int N, uint64_t d,
+                            uint64_t bucket_elems, int bits, int accumulate,
+                            float* out_dev, void* stream);
+
+/* Text for a return code (static storage). */
+const char* tq_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TQ_H */

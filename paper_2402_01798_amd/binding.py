@@ -1,0 +1,182 @@
+"""Thin ctypes layer over ``libtq.so``: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used purely as device memory; every call passes
+``data_ptr()`` values and the current HIP stream to the library.  There is no fallback:
+if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libtq.so")
+
+OK, EINVAL, EALIGN, EUNSUPPORTED, EHIP = 0, 1, 2, 3, 4
+F32, BF16 = 0, 1
+GRID_UNIFORM, GRID_NONUNIFORM = 0, 1
+NBINS = 898
+MAX_WORKERS = 64
+STATS_BYTES = 3632
+PARAMS_BYTES = 160
+
+# numpy views of the interface structs (layout fixed by include/tq.h)
+STATS_DTYPE = np.dtype([
+    ("hist", np.uint32, (NBINS,)), ("n_nonfinite", np.uint32), ("absmax", np.float32),
+    ("n", np.uint64), ("g_min", np.float32), ("reserved", np.uint32),
+    ("n_tail", np.uint64), ("sum_log_tail", np.float64)], align=True)
+PARAMS_DTYPE = np.dtype([
+    ("alpha", np.float32), ("bits", np.uint32), ("s", np.uint32), ("grid", np.uint32),
+    ("level", np.float32, (16,)), ("inv_w", np.float32, (16,)),
+    ("gamma_hat", np.float32), ("rho_hat", np.float32), ("g_min", np.float32),
+    ("flags", np.uint32)], align=True)
+assert STATS_DTYPE.itemsize == STATS_BYTES and PARAMS_DTYPE.itemsize == PARAMS_BYTES
+
+
+class TqError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__("%s: %s (code %d)" % (what, strerror(code), code))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s not found: build it with `python -m paper_2402_01798_amd.build`" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        u64, u32, i32, f32, vp = C.c_uint64, C.c_uint32, C.c_int, C.c_float, C.c_void_p
+        L.tq_num_buckets.argtypes = [u64, u64]
+        L.tq_num_buckets.restype = u64
+        L.tq_payload_bytes.argtypes = [u64, i32]
+        L.tq_payload_bytes.restype = u64
+        L.tq_stats.argtypes = [vp, i32, u64, u64, f32, vp, vp]
+        L.tq_params.argtypes = [vp, u64, i32, i32, f32, vp, vp]
+        L.tq_compress.argtypes = [vp, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
+        L.tq_decompress_aggregate.argtypes = [vp, vp, vp, i32, u64, u64, i32, i32, vp, vp]
+        L.tq_strerror.argtypes = [i32]
+        L.tq_strerror.restype = C.c_char_p
+        for f in (L.tq_stats, L.tq_params, L.tq_compress, L.tq_decompress_aggregate):
+            f.restype = i32
+        _lib = L
+    return _lib
+
+
+def strerror(code):
+    return lib().tq_strerror(code).decode()
+
+
+def _check(rc, what):
+    if rc != OK:
+        raise TqError(rc, what)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(g):
+    if g.dtype == torch.float32:
+        return F32
+    if g.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("gradient must be float32 or bfloat16, got %s" % g.dtype)
+
+
+def _dev(t, what):
+    if not (t.is_cuda and t.is_contiguous()):
+        raise ValueError("%s must be a contiguous device tensor" % what)
+    return C.c_void_p(t.data_ptr())
+
+
+def num_buckets(d, bucket_elems=0):
+    return int(lib().tq_num_buckets(d, bucket_elems))
+
+
+def payload_bytes(d, bits):
+    return int(lib().tq_payload_bytes(d, bits))
+
+
+def alloc_stats(d, bucket_elems=0, device="cuda"):
+    return torch.empty(num_buckets(d, bucket_elems) * STATS_BYTES, dtype=torch.uint8, device=device)
+
+
+def alloc_params(d, bucket_elems=0, device="cuda"):
+    return torch.empty(num_buckets(d, bucket_elems) * PARAMS_BYTES, dtype=torch.uint8, device=device)
+
+
+def alloc_payload(d, bits, device="cuda"):
+    return torch.empty(payload_bytes(d, bits), dtype=torch.uint8, device=device)
+
+
+def tq_stats(g, stats, bucket_elems=0, g_min=0.0):
+    _check(lib().tq_stats(_dev(g, "g"), _dtype_code(g), g.numel(), bucket_elems, g_min,
+                          _dev(stats, "stats"), _stream()), "tq_stats")
+    return stats
+
+
+def tq_params(stats, params, bits, grid, alpha_override=0.0):
+    nb = stats.numel() // STATS_BYTES
+    if params.numel() != nb * PARAMS_BYTES:
+        raise ValueError("params buffer does not match the number of buckets")
+    _check(lib().tq_params(_dev(stats, "stats"), nb, bits, grid, alpha_override,
+                           _dev(params, "params"), _stream()), "tq_params")
+    return params
+
+
+def tq_compress(g, params, payload, bits, seed, worker, step, bucket_elems=0):
+    d = g.numel()
+    if params.numel() != num_buckets(d, bucket_elems) * PARAMS_BYTES:
+        raise ValueError("params buffer does not match the number of buckets")
+    if payload.numel() < payload_bytes(d, bits):
+        raise ValueError("payload buffer too small")
+    _check(lib().tq_compress(_dev(g, "g"), _dtype_code(g), d, bucket_elems, _dev(params, "params"),
+                             bits, seed, worker, step, _dev(payload, "payload"), _stream()),
+           "tq_compress")
+    return payload
+
+
+def tq_decompress_aggregate(payloads, params, out, bits, bucket_elems=0, weights=None,
+                            accumulate=False):
+    N = len(payloads)
+    d = out.numel()
+    if len(params) != N:
+        raise ValueError("one params buffer per payload")
+    if out.dtype != torch.float32:
+        raise TypeError("out must be float32")
+    nb = num_buckets(d, bucket_elems)
+    for p, q in zip(payloads, params):
+        if p.numel() < payload_bytes(d, bits) or q.numel() != nb * PARAMS_BYTES:
+            raise ValueError("payload / params buffer size does not match d")
+    pp = (C.c_void_p * N)(*[_dev(p, "payload").value for p in payloads])
+    qq = (C.c_void_p * N)(*[_dev(q, "params").value for q in params])
+    ww = None
+    if weights is not None:
+        if len(weights) != N:
+            raise ValueError("one weight per worker")
+        ww = (C.c_float * N)(*[float(w) for w in weights])
+    _check(lib().tq_decompress_aggregate(pp, qq, ww, N, d, bucket_elems, bits, int(bool(accumulate)),
+                                         _dev(out, "out"), _stream()), "tq_decompress_aggregate")
+    return out
+
+
+def stats_to_numpy(stats):
+    """Host copy of a stats buffer as a structured array (synchronises)."""
+    return stats.cpu().numpy().view(STATS_DTYPE)
+
+
+def params_to_numpy(params):
+    """Host copy of a params buffer as a structured array (synchronises)."""
+    return params.cpu().numpy().view(PARAMS_DTYPE)
+
+
+def params_from_numpy(arr, device="cuda"):
+    """Device buffer holding the given PARAMS_DTYPE-compatible records (same byte layout)."""
+    raw = np.ascontiguousarray(arr).view(np.uint8).reshape(-1)
+    return torch.from_numpy(raw.copy()).to(device)

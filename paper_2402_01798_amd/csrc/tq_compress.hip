@@ -1,0 +1,198 @@
+// tq_compress: Alg. 1 client step of arXiv 2402.01798 -- truncate (Eq. 1), locate the cell
+// and its rounding probability, round stochastically (Eq. 2), pack b-bit codes.
+//
+// One lane owns 8 consecutive elements: they share one Philox4x32-10 call (8 x 16 random
+// bits) and their codes are exactly b bytes of the payload, so a wavefront reads 2 KiB
+// (fp32) or 1 KiB (bf16) of gradient and writes 64*b contiguous bytes.
+#include "tq_device.h"
+
+namespace tq {
+
+template <int DTYPE>
+__device__ __forceinline__ void load_group(const void* g, uint64_t e0, float (&x)[8])
+{
+    if constexpr (DTYPE == TQ_F32) {
+        const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(g) + e0);
+        const float4 a = p[0], b = p[1];
+        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+        x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    } else {
+        const uint4 v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(g) + e0);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __uint_as_float(w[i] << 16);
+            x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+}
+
+template <int DTYPE>
+__device__ __forceinline__ float load_one(const void* g, uint64_t e)
+{
+    if constexpr (DTYPE == TQ_F32) return static_cast<const float*>(g)[e];
+    return __uint_as_float((uint32_t) static_cast<const uint16_t*>(g)[e] << 16);
+}
+
+// Levels and inverse widths of one bucket, kept in LDS for the per-lane lookup of the
+// non-uniform path: entry k = (l_k, inv_w[k]).
+struct LevelLds {
+    float2 e[16];
+};
+
+template <int BITS, int GRID>
+__device__ __forceinline__ uint32_t quantize(float x, float rnd, float alpha, float inv_step,
+                                             const float (&lv)[16], const LevelLds& tab)
+{
+    constexpr uint32_t S = (1u << BITS) - 1u;
+    x = (x != x) ? 0.0f : x;                                   // NaN -> +0
+    const float xc = __builtin_amdgcn_fmed3f(x, -alpha, alpha);  // Eq. (1), x is not NaN here
+    uint32_t code;
+    if constexpr (GRID == TQ_GRID_UNIFORM) {
+        const float u = (xc + alpha) * inv_step;               // position in units of cells
+        const float v = u + rnd;                               // floor(v) = k + [rnd >= 1 - frac]
+        code = (uint32_t)v;
+        code = code > S ? S : code;
+    } else {
+        uint32_t k = 0;                                        // cell: l_k <= xc < l_{k+1}
+#pragma unroll
+        for (uint32_t j = 1; j < S; ++j) k += (xc >= lv[j]) ? 1u : 0u;
+        const float2 cell = tab.e[k];
+        const float frac = (xc - cell.x) * cell.y;             // p_r of Eq. (2)
+        const float v = frac + rnd;
+        uint32_t up = (uint32_t)v;
+        up = up > 1u ? 1u : up;
+        code = k + up;
+    }
+    return code;
+}
+
+// Codes of one lane's 8 elements, packed little-endian into the low 8*BITS bits.
+template <int BITS, int GRID>
+__device__ __forceinline__ uint32_t encode_group(const float (&x)[8], const uint32_t (&rw)[4], int n_valid,
+                                                 float alpha, float inv_step, const float (&lv)[16],
+                                                 const LevelLds& tab)
+{
+    uint32_t word = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t r = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
+        const float rnd = fmaf((float)r, 1.0f / 65536.0f, 1.0f / 131072.0f);   // (r + 1/2) 2^-16, exact
+        uint32_t code = quantize<BITS, GRID>(x[j], rnd, alpha, inv_step, lv, tab);
+        if (j >= n_valid) code = 0;                            // past the end: pad bits are zero
+        word |= code << (j * BITS);
+    }
+    return word;
+}
+
+template <int DTYPE, int BITS>
+__global__ __launch_bounds__(kBlock) void tq_compress_kernel(
+    const void* __restrict__ g, uint64_t d, uint64_t d_pad, uint64_t bucket_elems,
+    uint32_t tiles_per_bucket, const tq_params_t* __restrict__ params, uint32_t seed_lo,
+    uint32_t seed_hi, uint32_t worker, uint32_t step, uint8_t* __restrict__ payload,
+    uint64_t payload_bytes)
+{
+    const TileGeom t = tile_geom(blockIdx.x, d_pad, bucket_elems, tiles_per_bucket);
+    if (t.ebase >= t.eend) return;                             // idle tile of a short last bucket
+    const tq_params_t* P = params + t.bucket;
+
+    __shared__ LevelLds tab;
+    float lv[16];
+    const float alpha = P->alpha;
+    const float inv_step = P->inv_w[0];
+    const bool nonuniform = P->grid != TQ_GRID_UNIFORM;        // uniform over the workgroup
+    if (nonuniform) {
+        if (threadIdx.x < 16) tab.e[threadIdx.x] = make_float2(P->level[threadIdx.x], P->inv_w[threadIdx.x]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) lv[j] = P->level[j];       // wave-uniform: scalar loads
+        __syncthreads();
+    }
+
+    const uint64_t e0 = t.ebase + (uint64_t)threadIdx.x * kGroup;
+    const uint64_t qb = t.ebase >> 3;                          // first group of the tile (uniform)
+    const uint32_t qb_lo = (uint32_t)qb, qb_hi = (uint32_t)(qb >> 32);
+    const uint32_t q_lo = qb_lo + threadIdx.x;
+    const uint64_t byte_off = (qb + threadIdx.x) * (uint64_t)BITS;
+    if (e0 >= t.eend || byte_off >= payload_bytes) return;
+
+    uint32_t word = 0;
+    if (e0 < d) {
+        uint32_t rw[4];
+        if (qb_lo <= 0xFFFFFFFFu - kBlock) {                   // no carry inside this tile:
+            philox4x32_10(q_lo, qb_hi, worker, step, seed_lo, seed_hi, rw);  // high word stays scalar
+        } else {
+            philox4x32_10(q_lo, qb_hi + (q_lo < qb_lo ? 1u : 0u), worker, step, seed_lo, seed_hi, rw);
+        }
+        float x[8];
+        const int n_valid = (d - e0 >= (uint64_t)kGroup) ? kGroup : (int)(d - e0);
+        if (n_valid == kGroup) {
+            load_group<DTYPE>(g, e0, x);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, e0 + j) : 0.0f;
+        }
+        word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM>(x, rw, n_valid, alpha, inv_step, lv, tab)
+                          : encode_group<BITS, TQ_GRID_UNIFORM>(x, rw, n_valid, alpha, inv_step, lv, tab);
+    }
+
+    uint8_t* out = payload + byte_off;
+    if constexpr (BITS == 4) {
+        *reinterpret_cast<uint32_t*>(out) = word;
+    } else if constexpr (BITS == 2) {
+        *reinterpret_cast<uint16_t*>(out) = (uint16_t)word;
+    } else {
+        out[0] = (uint8_t)word;
+        out[1] = (uint8_t)(word >> 8);
+        out[2] = (uint8_t)(word >> 16);
+    }
+}
+
+}  // namespace tq
+
+namespace {
+
+template <int DTYPE>
+hipError_t launch(int bits, dim3 blocks, hipStream_t st, const void* g, uint64_t d, uint64_t d_pad,
+                  uint64_t be, uint32_t tpb, const tq_params_t* params, uint64_t seed, uint32_t worker,
+                  uint32_t step, uint8_t* payload, uint64_t pbytes)
+{
+    const uint32_t slo = (uint32_t)seed, shi = (uint32_t)(seed >> 32);
+    const dim3 threads(tq::kBlock);
+    switch (bits) {
+        case 2:
+            hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 2>), blocks, threads, 0, st, g, d, d_pad, be, tpb,
+                               params, slo, shi, worker, step, payload, pbytes);
+            break;
+        case 3:
+            hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 3>), blocks, threads, 0, st, g, d, d_pad, be, tpb,
+                               params, slo, shi, worker, step, payload, pbytes);
+            break;
+        default:
+            hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 4>), blocks, threads, 0, st, g, d, d_pad, be, tpb,
+                               params, slo, shi, worker, step, payload, pbytes);
+            break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Host side of tq_compress after the argument checks of the C entry point.
+hipError_t tq_launch_compress(const void* g, int dtype, uint64_t d, uint64_t bucket_elems,
+                              const tq_params_t* params, int bits, uint64_t seed, uint32_t worker,
+                              uint32_t step, void* payload, hipStream_t st)
+{
+    const uint64_t d_pad = (d + 127) / 128 * 128;
+    const uint64_t be = bucket_elems ? bucket_elems : d_pad;
+    const uint64_t nb = (d_pad + be - 1) / be;
+    const uint64_t tpb = (be + tq::kTile - 1) / tq::kTile;
+    const uint64_t nblocks = nb * tpb;
+    if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const uint64_t pbytes = tq_payload_bytes(d, bits);
+    const dim3 blocks((unsigned)nblocks);
+    if (dtype == TQ_F32)
+        return launch<TQ_F32>(bits, blocks, st, g, d, d_pad, be, (uint32_t)tpb, params, seed, worker, step,
+                              static_cast<uint8_t*>(payload), pbytes);
+    return launch<TQ_BF16>(bits, blocks, st, g, d, d_pad, be, (uint32_t)tpb, params, seed, worker, step,
+                           static_cast<uint8_t*>(payload), pbytes);
+}

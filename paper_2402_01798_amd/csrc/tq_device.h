@@ -1,0 +1,61 @@
+// Device-side helpers shared by the gfx950 kernels of libtq.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tq.h"
+
+namespace tq {
+
+constexpr int kGroup = 8;            // elements served by one Philox4x32 call = one lane's work item
+constexpr int kBlock = 256;          // threads per workgroup (4 wavefronts of 64)
+constexpr int kTile = kBlock * kGroup;  // elements per workgroup tile (2048)
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies whose
+// halves are crossed over and xored with a Weyl-sequence round key.  Operands that are
+// uniform over the wavefront (key, worker, step, high counter word) stay in SGPRs and
+// their multiplies run on the scalar unit; only the lane's counter word is per-lane.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Tile geometry shared by compress and decode.  Workgroup `blk` owns elements
+// [ebase, ebase + kTile) of bucket `bucket`, cut at `eend` (the bucket's end, the last
+// bucket's end being d rounded up to a multiple of 128 so the payload padding is covered).
+struct TileGeom {
+    uint64_t bucket;
+    uint64_t ebase;
+    uint64_t eend;
+};
+
+__device__ __forceinline__ TileGeom tile_geom(uint32_t blk, uint64_t d_pad, uint64_t bucket_elems,
+                                              uint32_t tiles_per_bucket)
+{
+    TileGeom t;
+    const uint32_t b = blk / tiles_per_bucket;
+    const uint32_t tile = blk - b * tiles_per_bucket;
+    t.bucket = b;
+    const uint64_t bstart = (uint64_t)b * bucket_elems;
+    t.ebase = bstart + (uint64_t)tile * kTile;
+    const uint64_t bend = bstart + bucket_elems;
+    t.eend = bend < d_pad ? bend : d_pad;
+    return t;
+}
+
+}  // namespace tq

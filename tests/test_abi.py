@@ -1,0 +1,90 @@
+"""The C-ABI library loads, exports every symbol include/tq.h declares, and rejects bad
+arguments before touching a device (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tq.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2402_01798_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()                  # only when nothing is built; normally built beforehand
+    return binding.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tq_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert set(names) == {"tq_num_buckets", "tq_payload_bytes", "tq_stats", "tq_params",
+                          "tq_compress", "tq_decompress_aggregate", "tq_strerror"}
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_struct_sizes_match_the_oracle_side_layout():
+    from oracle import binding as O
+    from paper_2402_01798_amd import binding as B
+    assert B.STATS_DTYPE.itemsize == O.STATS_DTYPE.itemsize == 3632
+    assert B.PARAMS_DTYPE.itemsize == O.PARAMS_DTYPE.itemsize == 160
+    assert B.STATS_DTYPE.fields.keys() == O.STATS_DTYPE.fields.keys()
+    for k in B.PARAMS_DTYPE.fields:
+        assert B.PARAMS_DTYPE.fields[k][1] == O.PARAMS_DTYPE.fields[k][1]
+    for k in B.STATS_DTYPE.fields:
+        assert B.STATS_DTYPE.fields[k][1] == O.STATS_DTYPE.fields[k][1]
+
+
+def test_host_arithmetic(L):
+    from oracle import binding as O
+    for d, be in [(1, 0), (61706, 0), (1000, 384), (1 << 20, 1 << 20), (25_600_000, 1 << 20)]:
+        assert L.tq_num_buckets(d, be) == O.num_buckets(d, be)
+    for d in (1, 7, 8, 9, 127, 128, 61706, 11_200_000, 10 ** 9):
+        for b in (2, 3, 4):
+            assert L.tq_payload_bytes(d, b) == O.payload_bytes(d, b)
+    assert L.tq_payload_bytes(61706, 3) == 23152
+
+
+def test_bad_arguments_are_rejected_without_a_device(L):
+    from paper_2402_01798_amd import binding as B
+    p = C.c_void_p(0x1000)             # never dereferenced: every call below fails its checks
+    odd = C.c_void_p(0x1004)
+    assert L.tq_stats(p, 0, 0, 0, 0.0, p, None) == B.EINVAL                  # d = 0
+    assert L.tq_stats(p, 7, 100, 0, 0.0, p, None) == B.EINVAL                # dtype
+    assert L.tq_stats(p, 0, 1000, 100, 0.0, p, None) == B.EINVAL             # bucket not multiple of 128
+    assert L.tq_stats(p, 0, 1000, 0, 1e-20, p, None) == B.EINVAL             # g_min below the histogram
+    assert L.tq_stats(odd, 0, 1000, 0, 0.0, p, None) == B.EALIGN
+    assert L.tq_stats(None, 0, 1000, 0, 0.0, p, None) == B.EINVAL
+    assert L.tq_params(p, 1, 5, 0, 0.0, p, None) == B.EINVAL                 # bits
+    assert L.tq_params(p, 1, 3, 2, 0.0, p, None) == B.EINVAL                 # grid
+    assert L.tq_params(p, 0, 3, 0, 0.0, p, None) == B.EINVAL                 # no buckets
+    assert L.tq_params(p, 1, 3, 0, float("nan"), p, None) == B.EINVAL
+    assert L.tq_compress(p, 0, 1000, 0, p, 1, 0, 0, 0, p, None) == B.EINVAL  # bits
+    assert L.tq_compress(p, 0, 1000, 0, p, 3, 0, 0, 0, odd, None) == B.EALIGN
+    assert L.tq_compress(p, 0, 1 << 41, 0, p, 3, 0, 0, 0, p, None) == B.EUNSUPPORTED
+    arr = (C.c_void_p * 2)(0x1000, 0x2000)
+    assert L.tq_decompress_aggregate(arr, arr, None, 0, 1000, 0, 3, 0, p, None) == B.EINVAL    # N = 0
+    assert L.tq_decompress_aggregate(arr, arr, None, 65, 1000, 0, 3, 0, p, None) == B.EUNSUPPORTED
+    assert L.tq_decompress_aggregate(arr, arr, None, 2, 1000, 0, 3, 0, odd, None) == B.EALIGN
+    bad = (C.c_void_p * 2)(0x1000, 0)
+    assert L.tq_decompress_aggregate(bad, arr, None, 2, 1000, 0, 3, 0, p, None) == B.EINVAL    # null payload
+    assert L.tq_strerror(B.EALIGN).decode().startswith("device pointer")
+
+
+def test_product_path_has_no_oracle_dependency():
+    """The package must not import the oracle (it is test infrastructure)."""
+    pkg = os.path.join(ROOT, "paper_2402_01798_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f

@@ -1,0 +1,93 @@
+"""tq_compress on the GPU against the oracle: packed bytes must be identical."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import binding as O
+from paper_2402_01798_amd import binding as B
+from gpu_common import device_compress, oracle_params, small_gradient
+
+pytestmark = pytest.mark.gpu
+
+# sizes that span several 2048-element tiles and leave ragged tails of every kind
+SIZES = [1, 5, 8, 9, 127, 128, 2047, 2048, 2049, 61_706, 3 * 2048 * 7 + 1234]
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("grid", [B.GRID_UNIFORM, B.GRID_NONUNIFORM])
+@pytest.mark.parametrize("d", SIZES)
+def test_bytes_match_oracle_fp32(bits, grid, d):
+    g_dev, g_np = small_gradient("cfg1", 1, d)
+    P = oracle_params(g_np, bits, grid, g_min=1e-4 if d > 1000 else 0.0)
+    got = device_compress(g_dev, P, bits, seed=0xC0FFEE1234, worker=1, step=3).cpu().numpy()
+    want = O.compress(g_np, P, 0xC0FFEE1234, 1, 3)
+    assert got.size == want.size
+    assert (got == want).all()
+
+
+@pytest.mark.parametrize("bits,grid", [(2, B.GRID_NONUNIFORM), (3, B.GRID_UNIFORM), (4, B.GRID_NONUNIFORM)])
+@pytest.mark.parametrize("d", [9, 4100, 70_001])
+def test_bytes_match_oracle_bf16(bits, grid, d):
+    g_dev, g_np = small_gradient("cfg5", 0, d)
+    assert g_dev.dtype == torch.bfloat16 and g_np.dtype == np.uint16
+    P = oracle_params(g_np, bits, grid, g_min=1e-6)
+    got = device_compress(g_dev, P, bits, 77, 0, 0).cpu().numpy()
+    assert (got == O.compress(g_np, P, 77, 0, 0)).all()
+
+
+@pytest.mark.parametrize("bits,grid", [(3, B.GRID_NONUNIFORM), (2, B.GRID_UNIFORM), (4, B.GRID_UNIFORM)])
+@pytest.mark.parametrize("d,bucket", [(10_000, 2048), (10_000, 128), (3 * 4096, 4096), (70_000, 16_384), (5000, 8192)])
+def test_buckets_match_oracle(bits, grid, d, bucket):
+    g_dev, g_np = small_gradient("cfg4", 2, d)       # per-layer scales: buckets really differ
+    P = oracle_params(g_np, bits, grid, bucket_elems=bucket)
+    assert P.size == -(-d // bucket)
+    got = device_compress(g_dev, P, bits, 5, 2, 9, bucket_elems=bucket).cpu().numpy()
+    assert (got == O.compress(g_np, P, 5, 2, 9, bucket_elems=bucket)).all()
+
+
+def test_special_values_and_seed_worker_step():
+    d = 4096 + 37
+    g_dev, g_np = small_gradient("cfg1", 0, d)
+    g_np = g_np.copy()
+    g_np[[0, 1, 2, 3, 4, 2050, d - 1]] = [np.nan, np.inf, -np.inf, 0.0, -0.0, np.nan, np.inf]
+    g_np[10:20] = np.float32(1e-42)                   # denormals
+    g_np[20:30] = [3e38, -3e38, 1e-30, -1e-30, 7.07e-4, -7.07e-4, 1e-4, -1e-4, 2.5e-4, 0.5]
+    g_dev = torch.from_numpy(g_np).cuda()
+    for bits, grid in [(3, B.GRID_UNIFORM), (3, B.GRID_NONUNIFORM), (2, B.GRID_NONUNIFORM), (4, B.GRID_UNIFORM)]:
+        P = oracle_params(g_np, bits, grid, g_min=1e-4)
+        seen = set()
+        for seed, worker, step in [(0, 0, 0), (2 ** 64 - 1, 2 ** 32 - 1, 2 ** 32 - 1), (1, 0, 0), (0, 1, 0), (0, 0, 1)]:
+            got = device_compress(g_dev, P, bits, seed, worker, step).cpu().numpy()
+            assert (got == O.compress(g_np, P, seed, worker, step)).all()
+            seen.add(got.tobytes())
+        assert len(seen) == 5                        # every key component changes the stream
+
+
+def test_hand_made_asymmetric_codebook():
+    """The non-uniform path must follow any increasing table, not only mirrored ones."""
+    d = 9000
+    rng = np.random.default_rng(0)
+    g_np = (rng.standard_normal(d) * 0.6).astype(np.float32)
+    P = np.zeros(1, dtype=O.PARAMS_DTYPE)
+    lv = np.array([-1.0, -0.9, -0.1, 0.0, 0.05, 0.3, 0.31, 1.0], dtype=np.float32)
+    P["alpha"], P["bits"], P["s"], P["grid"] = 1.0, 3, 7, O.GRID_NONUNIFORM
+    P["level"][0, :8] = lv
+    P["inv_w"][0, :7] = (1.0 / np.diff(lv.astype(np.float64))).astype(np.float32)
+    got = device_compress(torch.from_numpy(g_np).cuda(), P, 3, 9, 9, 9).cpu().numpy()
+    assert (got == O.compress(g_np, P, 9, 9, 9)).all()
+    # a cell of zero width (inv_w = 0) is skipped, never divided by
+    lv2 = np.array([-1.0, -0.5, -0.5, 0.5], dtype=np.float32)
+    P2 = np.zeros(1, dtype=O.PARAMS_DTYPE)
+    P2["alpha"], P2["bits"], P2["s"], P2["grid"] = 1.0, 2, 3, O.GRID_NONUNIFORM
+    P2["level"][0, :4] = lv2
+    P2["inv_w"][0, :3] = [2.0, 0.0, 1.0]
+    got = device_compress(torch.from_numpy(g_np).cuda(), P2, 2, 1, 1, 1).cpu().numpy()
+    assert (got == O.compress(g_np, P2, 1, 1, 1)).all()
+
+
+def test_determinism_same_call_twice():
+    g_dev, g_np = small_gradient("cfg2", 3, 200_000)
+    P = oracle_params(g_np, 4, B.GRID_UNIFORM)
+    a = device_compress(g_dev, P, 4, 11, 3, 1).cpu().numpy()
+    b = device_compress(g_dev, P, 4, 11, 3, 1).cpu().numpy()
+    assert (a == b).all()

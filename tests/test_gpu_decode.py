@@ -1,0 +1,105 @@
+"""tq_decompress_aggregate on the GPU against the oracle (Alg. 1 server step)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import binding as O
+from paper_2402_01798_amd import binding as B
+from gpu_common import oracle_params, small_gradient
+
+pytestmark = pytest.mark.gpu
+
+
+def make_workers(wl, N, d, bits, grid, bucket=0, dtype=None):
+    gs, Ps, pays = [], [], []
+    for i in range(N):
+        _, g_np = small_gradient(wl, i, d, dtype=dtype)
+        P = oracle_params(g_np, bits, grid, bucket_elems=bucket)
+        gs.append(g_np)
+        Ps.append(P)
+        pays.append(O.compress(g_np, P, 1234, i, 7, bucket_elems=bucket))
+    return gs, Ps, pays
+
+
+def device_decode(pays, Ps, d, bits, bucket=0, weights=None, out=None):
+    dev_p = [torch.from_numpy(p).cuda() for p in pays]
+    dev_q = [B.params_from_numpy(P) for P in Ps]
+    accumulate = out is not None
+    if out is None:
+        out = torch.full((d,), float("nan"), dtype=torch.float32, device="cuda")
+    B.tq_decompress_aggregate(dev_p, dev_q, out, bits, bucket, weights, accumulate)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def close_enough(got, want, Ps):
+    """Tolerance of the target: 1e-6 relative to the largest level that entered the sums."""
+    scale = max(float(P["alpha"].max()) for P in Ps)
+    return np.abs(got.astype(np.float64) - want.astype(np.float64)).max() <= 1e-6 * scale
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N", [1, 3, 4, 8, 16])
+@pytest.mark.parametrize("d", [1, 9, 2049, 61_706])
+def test_average_matches_oracle(bits, N, d):
+    grid = B.GRID_NONUNIFORM if bits == 3 else B.GRID_UNIFORM
+    gs, Ps, pays = make_workers("cfg1", N, d, bits, grid)
+    want = O.decompress_aggregate(pays, Ps, d, bits)
+    got = device_decode(pays, Ps, d, bits)
+    assert close_enough(got, want, Ps)
+    assert (got == want).all()           # same additions in the same order: identical in practice
+
+
+@pytest.mark.parametrize("bits,bucket,d", [(3, 2048, 10_000), (2, 128, 5000), (4, 16_384, 70_000), (3, 1 << 20, (1 << 20) + 4321)])
+def test_buckets(bits, bucket, d):
+    gs, Ps, pays = make_workers("cfg4", 4, d, bits, B.GRID_NONUNIFORM, bucket=bucket)
+    want = O.decompress_aggregate(pays, Ps, d, bits, bucket_elems=bucket)
+    got = device_decode(pays, Ps, d, bits, bucket=bucket)
+    assert close_enough(got, want, Ps) and (got == want).all()
+
+
+def test_weights_and_accumulate():
+    d, bits, N = 33_333, 4, 5
+    gs, Ps, pays = make_workers("cfg2", N, d, bits, B.GRID_UNIFORM)
+    w = [0.1, 0.2, 0.3, 0.25, 0.15]
+    want = O.decompress_aggregate(pays, Ps, d, bits, weights=w)
+    got = device_decode(pays, Ps, d, bits, weights=w)
+    assert close_enough(got, want, Ps) and (got == want).all()
+    base = np.random.default_rng(0).standard_normal(d).astype(np.float32)
+    want = O.decompress_aggregate(pays, Ps, d, bits, out=base.copy())
+    got = device_decode(pays, Ps, d, bits, out=torch.from_numpy(base).cuda())
+    assert (got == want).all()
+
+
+def test_max_workers_and_beyond():
+    d, bits = 5000, 2
+    gs, Ps, pays = make_workers("cfg1", 2, d, bits, B.GRID_UNIFORM)
+    pays64, Ps64 = (pays * 32), (Ps * 32)
+    want = O.decompress_aggregate(pays64, Ps64, d, bits)
+    got = device_decode(pays64, Ps64, d, bits)
+    assert (got == want).all()
+    with pytest.raises(B.TqError) as e:
+        device_decode(pays * 33, Ps * 33, d, bits)
+    assert e.value.code == B.EUNSUPPORTED
+
+
+def test_round_trip_is_unbiased_for_the_truncated_gradient():
+    """End to end on the device: averaging many independently rounded workers approaches
+    T_alpha(g) (Lemma 1 through the whole GPU path)."""
+    d, bits, N = 20_000, 3, 64
+    g_dev, g_np = small_gradient("cfg1", 0, d)
+    P = oracle_params(g_np, bits, B.GRID_UNIFORM, g_min=1e-4)
+    params_dev = B.params_from_numpy(P)
+    pays = []
+    for i in range(N):
+        p = B.alloc_payload(d, bits)
+        B.tq_compress(g_dev, params_dev, p, bits, 99, i, 0)
+        pays.append(p)
+    out = torch.empty(d, dtype=torch.float32, device="cuda")
+    B.tq_decompress_aggregate(pays, [params_dev] * N, out, bits)
+    torch.cuda.synchronize()
+    alpha = float(P["alpha"][0])
+    width = 2 * alpha / 7
+    err = out.cpu().numpy().astype(np.float64) - np.clip(g_np, -alpha, alpha)
+    assert np.abs(err).max() < 6 * width / 2 / np.sqrt(N)
+    assert abs(err.mean()) < 4 * width / 2 / np.sqrt(N * d)

@@ -1,0 +1,134 @@
+"""The whole path on the GPU (stats -> params -> compress x N -> decode) against the oracle,
+on scaled-down and on full-size workloads of the benchmark spec."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import binding as O
+from oracle import params as OP
+from paper_2402_01798_amd import binding as B
+from paper_2402_01798_amd import synth
+from gpu_common import unpack_codes
+
+pytestmark = pytest.mark.gpu
+
+
+def run_device(wl, gs_dev, bits, grid, seed, step):
+    d = gs_dev[0].numel()
+    N = len(gs_dev)
+    stats = [B.alloc_stats(d, wl.bucket_elems) for _ in range(N)]
+    params = [B.alloc_params(d, wl.bucket_elems) for _ in range(N)]
+    pays = [B.alloc_payload(d, bits) for _ in range(N)]
+    out = torch.empty(d, dtype=torch.float32, device="cuda")
+    for i in range(N):
+        B.tq_stats(gs_dev[i], stats[i], wl.bucket_elems, wl.g_min)
+        B.tq_params(stats[i], params[i], bits, grid)
+        B.tq_compress(gs_dev[i], params[i], pays[i], bits, seed, i, step, wl.bucket_elems)
+    B.tq_decompress_aggregate(pays, params, out, bits, wl.bucket_elems)
+    torch.cuda.synchronize()
+    return stats, params, pays, out
+
+
+@pytest.mark.parametrize("name,d", [("cfg1", None), ("cfg2", 300_000), ("cfg3", (1 << 21) + 12_345),
+                                    ("cfg4", (3 << 20) + 999), ("cfg5", 1_000_003)])
+def test_whole_path_matches_oracle(name, d):
+    wl = synth.WORKLOADS[name]
+    d = wl.d if d is None else d
+    N = min(wl.workers, 4)
+    for bits in wl.bits:
+        for grid in wl.grids:
+            gs = [synth.make_gradient(wl, i, "cpu", d) for i in range(N)]
+            gs_dev = [g.cuda() for g in gs]
+            stats, params, pays, out = run_device(wl, gs_dev, bits, grid, seed=2024, step=5)
+            P_dev, pay_or = [], []
+            for i in range(N):
+                g_np = synth.as_numpy(gs[i])
+                S_or = O.stats(g_np, bucket_elems=wl.bucket_elems, g_min=wl.g_min)
+                S_dev = B.stats_to_numpy(stats[i]).view(O.STATS_DTYPE)
+                assert (S_dev["hist"] == S_or["hist"]).all() and (S_dev["absmax"] == S_or["absmax"]).all()
+                assert (S_dev["n_tail"] == S_or["n_tail"]).all()
+                P_or = OP.tq_params(S_or, bits, grid)
+                Pd = B.params_to_numpy(params[i]).view(O.PARAMS_DTYPE)
+                assert np.allclose(Pd["alpha"], P_or["alpha"], rtol=1e-6)
+                assert np.allclose(Pd["level"], P_or["level"], rtol=1e-6, atol=0)
+                assert (Pd["flags"] == P_or["flags"]).all()
+                # codes: the oracle encodes with the very parameter bytes the device produced
+                want = O.compress(g_np, Pd, 2024, i, 5, bucket_elems=wl.bucket_elems)
+                assert (pays[i].cpu().numpy() == want).all()
+                P_dev.append(Pd)
+                pay_or.append(want)
+            want_out = O.decompress_aggregate(pay_or, P_dev, d, bits, bucket_elems=wl.bucket_elems)
+            got_out = out.cpu().numpy()
+            scale = max(float(P["alpha"].max()) for P in P_dev)
+            assert np.abs(got_out.astype(np.float64) - want_out).max() <= 1e-6 * scale
+            assert (got_out == want_out).all()
+
+
+def test_cfg2_full_size_full_arrays():
+    """BASELINE config 2 at its full size (11.2 M x 8 workers, uniform 2- and 4-bit), in the
+    launch configuration the benchmark times; every byte and every average is compared."""
+    wl = synth.WORKLOADS["cfg2"]
+    gs_dev = [synth.make_gradient(wl, i, "cuda") for i in range(wl.workers)]
+    for bits in wl.bits:
+        stats, params, pays, out = run_device(wl, gs_dev, bits, B.GRID_UNIFORM, seed=7, step=1)
+        P_dev, pay_or = [], []
+        for i in range(wl.workers):
+            g_np = synth.as_numpy(gs_dev[i])
+            S_dev = B.stats_to_numpy(stats[i]).view(O.STATS_DTYPE)
+            assert S_dev.tobytes() == O.stats(g_np).tobytes()
+            Pd = B.params_to_numpy(params[i]).view(O.PARAMS_DTYPE)
+            want = O.compress(g_np, Pd, 7, i, 1)
+            assert (pays[i].cpu().numpy() == want).all()
+            P_dev.append(Pd)
+            pay_or.append(want)
+            print("cfg2 b=%d worker %d ok" % (bits, i), flush=True)
+        want_out = O.decompress_aggregate(pay_or, P_dev, wl.d, bits)
+        assert (out.cpu().numpy() == want_out).all()
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+def test_large_configs_sampled(name):
+    """BASELINE configs 3-5 at full size: statistics compared in full where the oracle is
+    quick, codes and averages on sampled elements computed by the oracle one at a time."""
+    wl = synth.WORKLOADS[name]
+    N = wl.workers if name != "cfg3" else 4            # 4 of the 16 workers keep the run short
+    bits, grid = wl.bits[0], wl.grids[-1]
+    gs_dev = [synth.make_gradient(wl, i, "cuda") for i in range(N)]
+    print(name, "generated", flush=True)
+    stats, params, pays, out = run_device(wl, gs_dev, bits, grid, seed=31337, step=2)
+    rng = np.random.default_rng(5)
+    d = wl.d
+    idx = np.unique(np.concatenate([
+        rng.integers(0, d, size=3000), np.arange(0, 64), np.arange(d - 64, d),
+        (np.arange(1, 6) * (wl.bucket_elems or 2048))[:, None].repeat(2, 1).ravel() - np.array([1, 0] * 5)]))
+    idx = idx[(idx >= 0) & (idx < d)]
+    idx_dev = torch.from_numpy(idx).cuda()
+    P_dev = [B.params_to_numpy(p).view(O.PARAMS_DTYPE) for p in params]
+    levels = np.zeros((N, idx.size), dtype=np.float32)
+    be = wl.bucket_elems
+    for i in range(N):
+        x = gs_dev[i][idx_dev].float().cpu().numpy()
+        pay = pays[i].cpu().numpy()
+        got = unpack_codes(pay, d, bits, idx)
+        for t, e in enumerate(idx):
+            P = P_dev[i][int(e) // be if be else 0: (int(e) // be if be else 0) + 1]
+            want = O.quantize_one(float(x[t]), P, O.rand16(31337, i, 2, int(e)))
+            assert got[t] == want, (name, i, int(e))
+            levels[i, t] = P["level"][0][want]
+        if i == 0:
+            # statistics of worker 0, in full (one pass of the scalar oracle)
+            S_or = O.stats(synth.as_numpy(gs_dev[0]), bucket_elems=be, g_min=wl.g_min)
+            S_dev = B.stats_to_numpy(stats[0]).view(O.STATS_DTYPE)
+            assert (S_dev["hist"] == S_or["hist"]).all() and (S_dev["n_tail"] == S_or["n_tail"]).all()
+            assert (S_dev["absmax"] == S_or["absmax"]).all()
+            assert np.allclose(S_dev["sum_log_tail"], S_or["sum_log_tail"], rtol=1e-6)
+            P_or = OP.tq_params(S_or, bits, grid)
+            assert np.allclose(P_dev[0]["alpha"], P_or["alpha"], rtol=1e-6)
+            assert np.allclose(P_dev[0]["level"], P_or["level"], rtol=1e-6, atol=0)
+        print(name, "worker", i, "ok", flush=True)
+    acc = levels[0].copy()
+    for i in range(1, N):
+        acc = acc + levels[i]
+    want_out = acc * np.float32(1.0 / N)
+    got_out = out[idx_dev].cpu().numpy()
+    assert (got_out == want_out).all()
