@@ -84,12 +84,18 @@ uint64_t tq_payload_bytes(uint64_t d, int bits);
  *   g_dev      [d] gradient, TQ_F32 (float) or TQ_BF16 (uint16 bit patterns)
  *   g_min      > 0: also count and log-sum the elements with |g| > g_min
  *              (must be >= 2^-40); <= 0: leave the tail to tq_params
- *   stats_dev  [tq_num_buckets] written in full (zeroed, then reduced into
- *              with integer atomics; sum_log_tail with fp64 atomics, so its
- *              last bits depend on the order of arrival)
+ *   stats_dev  [tq_num_buckets] written in full; deterministic
+ *   workspace_dev, workspace_bytes
+ *              caller-owned device scratch of at least
+ *              tq_stats_workspace_bytes(d, bucket_elems) bytes (partial
+ *              histograms of the workgroups); need not be cleared, contents
+ *              undefined afterwards; calls sharing one workspace must be
+ *              ordered on one stream
  */
+uint64_t tq_stats_workspace_bytes(uint64_t d, uint64_t bucket_elems);
 int tq_stats(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
-             float g_min, tq_stats_t* stats_dev, void* stream);
+             float g_min, tq_stats_t* stats_dev, void* workspace_dev,
+             uint64_t workspace_bytes, void* stream);
 
 /*
  * tq_params -- the two parameters of the quantizer, per bucket (Sec. IV):
@@ -123,6 +129,26 @@ int tq_params(const tq_stats_t* stats_dev, uint64_t nb, int bits, int grid,
 int tq_compress(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
                 const tq_params_t* params_dev, int bits, uint64_t seed,
                 uint32_t worker, uint32_t step, void* payload_dev, void* stream);
+
+/*
+ * Batched forms for `count` tensors of the same shape (d, dtype, bucket_elems, bits) in one
+ * launch each: the N simulated workers of one GPU, or several equal-sized tensors of one
+ * worker.  The *_host arguments are host arrays of `count` device pointers, each with the
+ * meaning of the single-tensor call; tensor i of tq_compress_multi is worker
+ * first_worker + i.  tq_stats_multi needs count * tq_stats_workspace_bytes(d, bucket_elems)
+ * bytes of workspace.  count = 1 .. TQ_MAX_WORKERS.  Results are identical to `count`
+ * single-tensor calls.
+ */
+int tq_stats_multi(const void* const* g_host, int count, int dtype, uint64_t d,
+                   uint64_t bucket_elems, float g_min, tq_stats_t* const* stats_host,
+                   void* workspace_dev, uint64_t workspace_bytes, void* stream);
+int tq_params_multi(const tq_stats_t* const* stats_host, int count, uint64_t nb, int bits,
+                    int grid, float alpha_override, tq_params_t* const* params_host,
+                    void* stream);
+int tq_compress_multi(const void* const* g_host, int count, int dtype, uint64_t d,
+                      uint64_t bucket_elems, const tq_params_t* const* params_host, int bits,
+                      uint64_t seed, uint32_t first_worker, uint32_t step,
+                      void* const* payload_host, void* stream);
 
 /*
  * tq_decompress_aggregate -- Alg. 1 server step: out[e] = sum_i w_i L_i[c_i(e)]

@@ -20,17 +20,17 @@
  *
  * Precision: the paper fixes none.  The quantizer's decision "round up or
  * down" yields an integer code, so it is taken in the precision of the
- * kernel under test: IEEE-754 binary32, one rounding per written operation,
- * no fused multiply-add (build with -ffp-contract=off), no division and no
- * libm call on the per-element path.  Reductions compared by tolerance
- * (sum of logs) run in binary64.
+ * kernel under test: IEEE-754 binary32, one rounding per written operation
+ * (build with -ffp-contract=off; fmaf() where written is the correctly
+ * rounded fused multiply-add), no division on the per-element path.
+ * Reductions compared by tolerance (sum of logs) run in binary64.
  *
  * What the paper leaves open and this file fixes (readings, listed in the
  * design document as well):
  *   - "with probability p_r" (Eq. 2): a 16-bit uniform integer r drawn from
  *     the counter-based generator Philox4x32-10 (Salmon, Moraes, Dror, Shaw,
  *     SC'11) gives the dither rnd = (r + 1/2) / 2^16 and the code is
- *     k + floor(frac + rnd), i.e. "up" with probability frac to within 2^-17.
+ *     k + [frac + rnd >= 1], i.e. "up" with probability frac to within 2^-16.
  *   - "encode using b bits": codes are laid into one little-endian bit
  *     stream, element e at bits [e*b, e*b+b), padded with zero bits to a
  *     multiple of 16 bytes.
@@ -137,21 +137,20 @@ uint32_t tqo_quantize_one(float g, const tqo_params_t *P, uint32_t r)
     float x = g;
     if (x != x) x = 0.0f;                       /* NaN carries no information */
     const float xc = tqo_truncate(x, P->alpha);
-    const float rnd = ((float)r + 0.5f) * (1.0f / 65536.0f); /* exact */
+    const float rf = (float)r;                   /* 0 .. 65535, exact */
     uint32_t code;
     if (P->grid == TQO_GRID_UNIFORM) {
-        /* all cells have width 2 alpha / s: position in units of cells */
-        float u = (xc + P->alpha) * P->inv_w[0];
-        float v = u + rnd;                       /* floor(v) = k + [rnd >= 1 - frac] */
+        /* all cells have width 2 alpha / s: position in units of cells, measured
+         * from -alpha, plus the half-grain 2^-17 of the dither; then the dither */
+        float u = fmaf(xc, P->inv_w[0], 0.5f * (float)s + 1.0f / 131072.0f);
+        float v = fmaf(rf, 1.0f / 65536.0f, u);  /* floor(v) = k + [rnd >= 1 - frac] */
         code = (uint32_t)v;
     } else {
         uint32_t k = 0;                          /* cell index: l_k <= xc < l_{k+1} */
         for (uint32_t j = 1; j < s; ++j) k += (xc >= P->level[j]) ? 1u : 0u;
-        float frac = (xc - P->level[k]) * P->inv_w[k];   /* p_r of Eq. (2) */
-        float v = frac + rnd;
-        uint32_t up = (uint32_t)v;
-        if (up > 1u) up = 1u;
-        code = k + up;
+        float rnd = fmaf(rf, 1.0f / 65536.0f, 1.0f / 131072.0f);  /* (r + 1/2) / 2^16, exact */
+        float v = fmaf(xc - P->level[k], P->inv_w[k], rnd);       /* p_r of Eq. (2) + dither */
+        code = k + (v >= 1.0f ? 1u : 0u);
     }
     if (code > s) code = s;
     return code;

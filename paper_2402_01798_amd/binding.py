@@ -56,13 +56,19 @@ def lib():
         L.tq_num_buckets.restype = u64
         L.tq_payload_bytes.argtypes = [u64, i32]
         L.tq_payload_bytes.restype = u64
-        L.tq_stats.argtypes = [vp, i32, u64, u64, f32, vp, vp]
+        L.tq_stats_workspace_bytes.argtypes = [u64, u64]
+        L.tq_stats_workspace_bytes.restype = u64
+        L.tq_stats.argtypes = [vp, i32, u64, u64, f32, vp, vp, u64, vp]
         L.tq_params.argtypes = [vp, u64, i32, i32, f32, vp, vp]
         L.tq_compress.argtypes = [vp, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
         L.tq_decompress_aggregate.argtypes = [vp, vp, vp, i32, u64, u64, i32, i32, vp, vp]
         L.tq_strerror.argtypes = [i32]
         L.tq_strerror.restype = C.c_char_p
-        for f in (L.tq_stats, L.tq_params, L.tq_compress, L.tq_decompress_aggregate):
+        L.tq_stats_multi.argtypes = [vp, i32, i32, u64, u64, f32, vp, vp, u64, vp]
+        L.tq_params_multi.argtypes = [vp, i32, u64, i32, i32, f32, vp, vp]
+        L.tq_compress_multi.argtypes = [vp, i32, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
+        for f in (L.tq_stats, L.tq_params, L.tq_compress, L.tq_decompress_aggregate,
+                  L.tq_stats_multi, L.tq_params_multi, L.tq_compress_multi):
             f.restype = i32
         _lib = L
     return _lib
@@ -107,6 +113,14 @@ def alloc_stats(d, bucket_elems=0, device="cuda"):
     return torch.empty(num_buckets(d, bucket_elems) * STATS_BYTES, dtype=torch.uint8, device=device)
 
 
+def stats_workspace_bytes(d, bucket_elems=0):
+    return int(lib().tq_stats_workspace_bytes(d, bucket_elems))
+
+
+def alloc_stats_workspace(d, bucket_elems=0, device="cuda"):
+    return torch.empty(stats_workspace_bytes(d, bucket_elems), dtype=torch.uint8, device=device)
+
+
 def alloc_params(d, bucket_elems=0, device="cuda"):
     return torch.empty(num_buckets(d, bucket_elems) * PARAMS_BYTES, dtype=torch.uint8, device=device)
 
@@ -115,9 +129,10 @@ def alloc_payload(d, bits, device="cuda"):
     return torch.empty(payload_bytes(d, bits), dtype=torch.uint8, device=device)
 
 
-def tq_stats(g, stats, bucket_elems=0, g_min=0.0):
+def tq_stats(g, stats, workspace, bucket_elems=0, g_min=0.0):
     _check(lib().tq_stats(_dev(g, "g"), _dtype_code(g), g.numel(), bucket_elems, g_min,
-                          _dev(stats, "stats"), _stream()), "tq_stats")
+                          _dev(stats, "stats"), _dev(workspace, "workspace"), workspace.numel(),
+                          _stream()), "tq_stats")
     return stats
 
 
@@ -140,6 +155,39 @@ def tq_compress(g, params, payload, bits, seed, worker, step, bucket_elems=0):
                              bits, seed, worker, step, _dev(payload, "payload"), _stream()),
            "tq_compress")
     return payload
+
+
+def _ptr_array(tensors, what):
+    return (C.c_void_p * len(tensors))(*[_dev(t, what).value for t in tensors])
+
+
+def tq_stats_multi(gs, stats, workspace, bucket_elems=0, g_min=0.0):
+    """Batched tq_stats: lists of same-shaped gradients and their stats buffers."""
+    _check(lib().tq_stats_multi(_ptr_array(gs, "g"), len(gs), _dtype_code(gs[0]), gs[0].numel(),
+                                bucket_elems, g_min, _ptr_array(stats, "stats"),
+                                _dev(workspace, "workspace"), workspace.numel(), _stream()),
+           "tq_stats_multi")
+    return stats
+
+
+def tq_params_multi(stats, params, bits, grid, alpha_override=0.0):
+    nb = stats[0].numel() // STATS_BYTES
+    _check(lib().tq_params_multi(_ptr_array(stats, "stats"), len(stats), nb, bits, grid, alpha_override,
+                                 _ptr_array(params, "params"), _stream()), "tq_params_multi")
+    return params
+
+
+def tq_compress_multi(gs, params, payloads, bits, seed, first_worker, step, bucket_elems=0):
+    d = gs[0].numel()
+    for g, q, p in zip(gs, params, payloads):
+        if g.numel() != d or g.dtype != gs[0].dtype:
+            raise ValueError("batched tensors must share shape and dtype")
+        if q.numel() != num_buckets(d, bucket_elems) * PARAMS_BYTES or p.numel() < payload_bytes(d, bits):
+            raise ValueError("params / payload buffer size does not match d")
+    _check(lib().tq_compress_multi(_ptr_array(gs, "g"), len(gs), _dtype_code(gs[0]), d, bucket_elems,
+                                   _ptr_array(params, "params"), bits, seed, first_worker, step,
+                                   _ptr_array(payloads, "payload"), _stream()), "tq_compress_multi")
+    return payloads
 
 
 def tq_decompress_aggregate(payloads, params, out, bits, bucket_elems=0, weights=None,

@@ -4,13 +4,14 @@
 
 #include "tq.h"
 
-hipError_t tq_launch_stats(const void* g, int dtype, uint64_t d, uint64_t bucket_elems, float g_min,
-                           tq_stats_t* stats, hipStream_t st);
-hipError_t tq_launch_params(const tq_stats_t* stats, uint64_t nb, int bits, int grid, float alpha_override,
-                            tq_params_t* params, hipStream_t st);
-hipError_t tq_launch_compress(const void* g, int dtype, uint64_t d, uint64_t bucket_elems,
-                              const tq_params_t* params, int bits, uint64_t seed, uint32_t worker,
-                              uint32_t step, void* payload, hipStream_t st);
+hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
+                           float g_min, tq_stats_t* const* stats, void* workspace, hipStream_t st);
+uint64_t tq_stats_workspace_bytes_impl(uint64_t d, uint64_t bucket_elems);
+hipError_t tq_launch_params(const tq_stats_t* const* stats, int count, uint64_t nb, int bits, int grid,
+                            float alpha_override, tq_params_t* const* params, hipStream_t st);
+hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
+                              const tq_params_t* const* params, int bits, uint64_t seed, uint32_t first_worker,
+                              uint32_t step, void* const* payload, hipStream_t st);
 hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const* params,
                             const float* weights, int N, uint64_t d, uint64_t bucket_elems, int bits,
                             int accumulate, float* out, hipStream_t st);
@@ -51,41 +52,83 @@ uint64_t tq_payload_bytes(uint64_t d, int bits)
     return (nbytes + 15) / 16 * 16;
 }
 
-int tq_stats(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems, float g_min,
-             tq_stats_t* stats_dev, void* stream)
+uint64_t tq_stats_workspace_bytes(uint64_t d, uint64_t bucket_elems)
+{
+    if (check_layout(d, bucket_elems) != TQ_OK) return 0;
+    return tq_stats_workspace_bytes_impl(d, bucket_elems);
+}
+
+int tq_stats_multi(const void* const* g_host, int count, int dtype, uint64_t d, uint64_t bucket_elems,
+                   float g_min, tq_stats_t* const* stats_host, void* workspace_dev, uint64_t workspace_bytes,
+                   void* stream)
 {
     int rc;
     if ((rc = check_layout(d, bucket_elems)) || (rc = check_dtype(dtype))) return rc;
-    if (!g_dev || !stats_dev) return TQ_EINVAL;
+    if (count < 1 || !g_host || !stats_host || !workspace_dev) return TQ_EINVAL;
+    if (count > TQ_MAX_WORKERS) return TQ_EUNSUPPORTED;
+    if (workspace_bytes < (uint64_t)count * tq_stats_workspace_bytes_impl(d, bucket_elems)) return TQ_EINVAL;
     if (g_min != g_min || (g_min > 0.0f && g_min < 9.094947017729282e-13f) || g_min > 3.0e38f) return TQ_EINVAL;
-    if (!aligned16(g_dev) || !aligned16(stats_dev)) return TQ_EALIGN;
-    return from_hip(tq_launch_stats(g_dev, dtype, d, bucket_elems, g_min, stats_dev,
+    if (!aligned16(workspace_dev)) return TQ_EALIGN;
+    for (int i = 0; i < count; ++i) {
+        if (!g_host[i] || !stats_host[i]) return TQ_EINVAL;
+        if (!aligned16(g_host[i]) || !aligned16(stats_host[i])) return TQ_EALIGN;
+    }
+    return from_hip(tq_launch_stats(g_host, count, dtype, d, bucket_elems, g_min, stats_host, workspace_dev,
                                     static_cast<hipStream_t>(stream)));
+}
+
+int tq_stats(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems, float g_min,
+             tq_stats_t* stats_dev, void* workspace_dev, uint64_t workspace_bytes, void* stream)
+{
+    return tq_stats_multi(&g_dev, 1, dtype, d, bucket_elems, g_min, &stats_dev, workspace_dev, workspace_bytes,
+                          stream);
+}
+
+int tq_params_multi(const tq_stats_t* const* stats_host, int count, uint64_t nb, int bits, int grid,
+                    float alpha_override, tq_params_t* const* params_host, void* stream)
+{
+    int rc;
+    if ((rc = check_bits(bits))) return rc;
+    if (grid != TQ_GRID_UNIFORM && grid != TQ_GRID_NONUNIFORM) return TQ_EINVAL;
+    if (nb == 0 || count < 1 || !stats_host || !params_host) return TQ_EINVAL;
+    if (count > TQ_MAX_WORKERS) return TQ_EUNSUPPORTED;
+    if (alpha_override != alpha_override || alpha_override > 3.0e38f) return TQ_EINVAL;
+    for (int i = 0; i < count; ++i) {
+        if (!stats_host[i] || !params_host[i]) return TQ_EINVAL;
+        if (!aligned16(stats_host[i]) || !aligned16(params_host[i])) return TQ_EALIGN;
+    }
+    return from_hip(tq_launch_params(stats_host, count, nb, bits, grid, alpha_override, params_host,
+                                     static_cast<hipStream_t>(stream)));
 }
 
 int tq_params(const tq_stats_t* stats_dev, uint64_t nb, int bits, int grid, float alpha_override,
               tq_params_t* params_dev, void* stream)
 {
+    return tq_params_multi(&stats_dev, 1, nb, bits, grid, alpha_override, &params_dev, stream);
+}
+
+int tq_compress_multi(const void* const* g_host, int count, int dtype, uint64_t d, uint64_t bucket_elems,
+                      const tq_params_t* const* params_host, int bits, uint64_t seed, uint32_t first_worker,
+                      uint32_t step, void* const* payload_host, void* stream)
+{
     int rc;
-    if ((rc = check_bits(bits))) return rc;
-    if (grid != TQ_GRID_UNIFORM && grid != TQ_GRID_NONUNIFORM) return TQ_EINVAL;
-    if (nb == 0 || !stats_dev || !params_dev) return TQ_EINVAL;
-    if (alpha_override != alpha_override || alpha_override > 3.0e38f) return TQ_EINVAL;
-    if (!aligned16(stats_dev) || !aligned16(params_dev)) return TQ_EALIGN;
-    return from_hip(tq_launch_params(stats_dev, nb, bits, grid, alpha_override, params_dev,
-                                     static_cast<hipStream_t>(stream)));
+    if ((rc = check_layout(d, bucket_elems)) || (rc = check_dtype(dtype)) || (rc = check_bits(bits))) return rc;
+    if (count < 1 || !g_host || !params_host || !payload_host) return TQ_EINVAL;
+    if (count > TQ_MAX_WORKERS) return TQ_EUNSUPPORTED;
+    for (int i = 0; i < count; ++i) {
+        if (!g_host[i] || !params_host[i] || !payload_host[i]) return TQ_EINVAL;
+        if (!aligned16(g_host[i]) || !aligned16(params_host[i]) || !aligned16(payload_host[i])) return TQ_EALIGN;
+    }
+    return from_hip(tq_launch_compress(g_host, count, dtype, d, bucket_elems, params_host, bits, seed,
+                                       first_worker, step, payload_host, static_cast<hipStream_t>(stream)));
 }
 
 int tq_compress(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
                 const tq_params_t* params_dev, int bits, uint64_t seed, uint32_t worker, uint32_t step,
                 void* payload_dev, void* stream)
 {
-    int rc;
-    if ((rc = check_layout(d, bucket_elems)) || (rc = check_dtype(dtype)) || (rc = check_bits(bits))) return rc;
-    if (!g_dev || !params_dev || !payload_dev) return TQ_EINVAL;
-    if (!aligned16(g_dev) || !aligned16(params_dev) || !aligned16(payload_dev)) return TQ_EALIGN;
-    return from_hip(tq_launch_compress(g_dev, dtype, d, bucket_elems, params_dev, bits, seed, worker, step,
-                                       payload_dev, static_cast<hipStream_t>(stream)));
+    return tq_compress_multi(&g_dev, 1, dtype, d, bucket_elems, &params_dev, bits, seed, worker, step,
+                             &payload_dev, stream);
 }
 
 int tq_decompress_aggregate(const void* const* payload_host, const tq_params_t* const* params_host,

@@ -40,35 +40,35 @@ struct LevelLds {
     float2 e[16];
 };
 
+// Eq. (1) then Eq. (2) for one element; `rf` is the element's 16-bit draw as a float.
+// The dither is rnd = (rf + 1/2) / 2^16 and the code is k + [frac + rnd >= 1].
 template <int BITS, int GRID>
-__device__ __forceinline__ uint32_t quantize(float x, float rnd, float alpha, float inv_step,
+__device__ __forceinline__ uint32_t quantize(float x, float rf, float alpha, float inv_step,
                                              const float (&lv)[16], const LevelLds& tab)
 {
     constexpr uint32_t S = (1u << BITS) - 1u;
     x = (x != x) ? 0.0f : x;                                   // NaN -> +0
-    const float xc = __builtin_amdgcn_fmed3f(x, -alpha, alpha);  // Eq. (1), x is not NaN here
-    uint32_t code;
+    const float xc = __builtin_amdgcn_fmed3f(x, -alpha, alpha);  // Eq. (1); x is not NaN here
     if constexpr (GRID == TQ_GRID_UNIFORM) {
-        const float u = (xc + alpha) * inv_step;               // position in units of cells
-        const float v = u + rnd;                               // floor(v) = k + [rnd >= 1 - frac]
-        code = (uint32_t)v;
-        code = code > S ? S : code;
+        // position in units of cells from -alpha, plus the dither's half grain; then the draw
+        const float u = fmaf(xc, inv_step, 0.5f * (float)S + 1.0f / 131072.0f);
+        const float v = fmaf(rf, 1.0f / 65536.0f, u);          // floor(v) = k + [rnd >= 1 - frac]
+        const uint32_t code = (uint32_t)v;
+        return code > S ? S : code;
     } else {
         uint32_t k = 0;                                        // cell: l_k <= xc < l_{k+1}
 #pragma unroll
         for (uint32_t j = 1; j < S; ++j) k += (xc >= lv[j]) ? 1u : 0u;
         const float2 cell = tab.e[k];
-        const float frac = (xc - cell.x) * cell.y;             // p_r of Eq. (2)
-        const float v = frac + rnd;
-        uint32_t up = (uint32_t)v;
-        up = up > 1u ? 1u : up;
-        code = k + up;
+        const float rnd = fmaf(rf, 1.0f / 65536.0f, 1.0f / 131072.0f);   // exact
+        const float v = fmaf(xc - cell.x, cell.y, rnd);        // p_r of Eq. (2) + dither
+        return k + (v >= 1.0f ? 1u : 0u);
     }
-    return code;
 }
 
 // Codes of one lane's 8 elements, packed little-endian into the low 8*BITS bits.
-template <int BITS, int GRID>
+// PARTIAL: only the first n_valid elements exist; the others encode as 0 (pad bits).
+template <int BITS, int GRID, bool PARTIAL>
 __device__ __forceinline__ uint32_t encode_group(const float (&x)[8], const uint32_t (&rw)[4], int n_valid,
                                                  float alpha, float inv_step, const float (&lv)[16],
                                                  const LevelLds& tab)
@@ -77,9 +77,8 @@ __device__ __forceinline__ uint32_t encode_group(const float (&x)[8], const uint
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const uint32_t r = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
-        const float rnd = fmaf((float)r, 1.0f / 65536.0f, 1.0f / 131072.0f);   // (r + 1/2) 2^-16, exact
-        uint32_t code = quantize<BITS, GRID>(x[j], rnd, alpha, inv_step, lv, tab);
-        if (j >= n_valid) code = 0;                            // past the end: pad bits are zero
+        uint32_t code = quantize<BITS, GRID>(x[j], (float)r, alpha, inv_step, lv, tab);
+        if (PARTIAL && j >= n_valid) code = 0;
         word |= code << (j * BITS);
     }
     return word;
@@ -87,14 +86,18 @@ __device__ __forceinline__ uint32_t encode_group(const float (&x)[8], const uint
 
 template <int DTYPE, int BITS>
 __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
-    const void* __restrict__ g, uint64_t d, uint64_t d_pad, uint64_t bucket_elems,
-    uint32_t tiles_per_bucket, const tq_params_t* __restrict__ params, uint32_t seed_lo,
-    uint32_t seed_hi, uint32_t worker, uint32_t step, uint8_t* __restrict__ payload,
+    const PtrTable g_tab, uint64_t d, uint64_t d_pad, uint64_t bucket_elems,
+    uint32_t tiles_per_bucket, const PtrTable params_tab, uint32_t seed_lo,
+    uint32_t seed_hi, uint32_t first_worker, uint32_t step, const MutPtrTable payload_tab,
     uint64_t payload_bytes)
 {
     const TileGeom t = tile_geom(blockIdx.x, d_pad, bucket_elems, tiles_per_bucket);
     if (t.ebase >= t.eend) return;                             // idle tile of a short last bucket
-    const tq_params_t* P = params + t.bucket;
+    // blockIdx.y = tensor of the batch; its worker id keys the random draws
+    const void* __restrict__ g = g_tab.p[blockIdx.y];
+    uint8_t* __restrict__ payload = static_cast<uint8_t*>(payload_tab.p[blockIdx.y]);
+    const uint32_t worker = first_worker + blockIdx.y;
+    const tq_params_t* P = static_cast<const tq_params_t*>(params_tab.p[blockIdx.y]) + t.bucket;
 
     __shared__ LevelLds tab;
     float lv[16];
@@ -115,24 +118,30 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     const uint64_t byte_off = (qb + threadIdx.x) * (uint64_t)BITS;
     if (e0 >= t.eend || byte_off >= payload_bytes) return;
 
+    // One Philox call per lane; the high counter word stays scalar unless the low word
+    // wraps inside this tile.
+    auto draw = [&](uint32_t (&rw)[4]) {
+        if (qb_lo <= 0xFFFFFFFFu - kBlock) philox4x32_10(q_lo, qb_hi, worker, step, seed_lo, seed_hi, rw);
+        else philox4x32_10(q_lo, qb_hi + (q_lo < qb_lo ? 1u : 0u), worker, step, seed_lo, seed_hi, rw);
+    };
+
     uint32_t word = 0;
-    if (e0 < d) {
-        uint32_t rw[4];
-        if (qb_lo <= 0xFFFFFFFFu - kBlock) {                   // no carry inside this tile:
-            philox4x32_10(q_lo, qb_hi, worker, step, seed_lo, seed_hi, rw);  // high word stays scalar
-        } else {
-            philox4x32_10(q_lo, qb_hi + (q_lo < qb_lo ? 1u : 0u), worker, step, seed_lo, seed_hi, rw);
-        }
+    if (e0 + kGroup <= d) {
         float x[8];
-        const int n_valid = (d - e0 >= (uint64_t)kGroup) ? kGroup : (int)(d - e0);
-        if (n_valid == kGroup) {
-            load_group<DTYPE>(g, e0, x);
-        } else {
+        load_group<DTYPE>(g, e0, x);                            // in flight while the draw is computed
+        uint32_t rw[4];
+        draw(rw);
+        word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab)
+                          : encode_group<BITS, TQ_GRID_UNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab);
+    } else if (e0 < d) {                                       // ragged end of the tensor
+        const int n_valid = (int)(d - e0);
+        float x[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, e0 + j) : 0.0f;
-        }
-        word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM>(x, rw, n_valid, alpha, inv_step, lv, tab)
-                          : encode_group<BITS, TQ_GRID_UNIFORM>(x, rw, n_valid, alpha, inv_step, lv, tab);
+        for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, e0 + j) : 0.0f;
+        uint32_t rw[4];
+        draw(rw);
+        word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab)
+                          : encode_group<BITS, TQ_GRID_UNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab);
     }
 
     uint8_t* out = payload + byte_off;
@@ -152,24 +161,24 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
 namespace {
 
 template <int DTYPE>
-hipError_t launch(int bits, dim3 blocks, hipStream_t st, const void* g, uint64_t d, uint64_t d_pad,
-                  uint64_t be, uint32_t tpb, const tq_params_t* params, uint64_t seed, uint32_t worker,
-                  uint32_t step, uint8_t* payload, uint64_t pbytes)
+hipError_t launch(int bits, dim3 blocks, hipStream_t st, const tq::PtrTable& g, uint64_t d, uint64_t d_pad,
+                  uint64_t be, uint32_t tpb, const tq::PtrTable& params, uint64_t seed, uint32_t first_worker,
+                  uint32_t step, const tq::MutPtrTable& payload, uint64_t pbytes)
 {
     const uint32_t slo = (uint32_t)seed, shi = (uint32_t)(seed >> 32);
     const dim3 threads(tq::kBlock);
     switch (bits) {
         case 2:
             hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 2>), blocks, threads, 0, st, g, d, d_pad, be, tpb,
-                               params, slo, shi, worker, step, payload, pbytes);
+                               params, slo, shi, first_worker, step, payload, pbytes);
             break;
         case 3:
             hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 3>), blocks, threads, 0, st, g, d, d_pad, be, tpb,
-                               params, slo, shi, worker, step, payload, pbytes);
+                               params, slo, shi, first_worker, step, payload, pbytes);
             break;
         default:
             hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 4>), blocks, threads, 0, st, g, d, d_pad, be, tpb,
-                               params, slo, shi, worker, step, payload, pbytes);
+                               params, slo, shi, first_worker, step, payload, pbytes);
             break;
     }
     return hipGetLastError();
@@ -177,22 +186,24 @@ hipError_t launch(int bits, dim3 blocks, hipStream_t st, const void* g, uint64_t
 
 }  // namespace
 
-// Host side of tq_compress after the argument checks of the C entry point.
-hipError_t tq_launch_compress(const void* g, int dtype, uint64_t d, uint64_t bucket_elems,
-                              const tq_params_t* params, int bits, uint64_t seed, uint32_t worker,
-                              uint32_t step, void* payload, hipStream_t st)
+// Host side of tq_compress / tq_compress_multi after the argument checks of the C entry
+// points: `count` same-shaped tensors in one launch (grid.y), workers first_worker + 0..count-1.
+hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
+                              const tq_params_t* const* params, int bits, uint64_t seed, uint32_t first_worker,
+                              uint32_t step, void* const* payload, hipStream_t st)
 {
     const uint64_t d_pad = (d + 127) / 128 * 128;
     const uint64_t be = bucket_elems ? bucket_elems : d_pad;
     const uint64_t nb = (d_pad + be - 1) / be;
     const uint64_t tpb = (be + tq::kTile - 1) / tq::kTile;
     const uint64_t nblocks = nb * tpb;
-    if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (nblocks == 0 || nblocks > 0x7FFFFFFFull || count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
     const uint64_t pbytes = tq_payload_bytes(d, bits);
-    const dim3 blocks((unsigned)nblocks);
+    tq::PtrTable gt{}, pt{};
+    tq::MutPtrTable yt{};
+    for (int i = 0; i < count; ++i) { gt.p[i] = g[i]; pt.p[i] = params[i]; yt.p[i] = payload[i]; }
+    const dim3 blocks((unsigned)nblocks, (unsigned)count);
     if (dtype == TQ_F32)
-        return launch<TQ_F32>(bits, blocks, st, g, d, d_pad, be, (uint32_t)tpb, params, seed, worker, step,
-                              static_cast<uint8_t*>(payload), pbytes);
-    return launch<TQ_BF16>(bits, blocks, st, g, d, d_pad, be, (uint32_t)tpb, params, seed, worker, step,
-                           static_cast<uint8_t*>(payload), pbytes);
+        return launch<TQ_F32>(bits, blocks, st, gt, d, d_pad, be, (uint32_t)tpb, pt, seed, first_worker, step, yt, pbytes);
+    return launch<TQ_BF16>(bits, blocks, st, gt, d, d_pad, be, (uint32_t)tpb, pt, seed, first_worker, step, yt, pbytes);
 }

@@ -35,6 +35,16 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// Pointer table of a batched launch: blockIdx.y selects the tensor (one simulated worker, or
+// one of several same-shaped tensors of one worker).  Passed by value in the kernel arguments.
+constexpr int kMaxBatch = TQ_MAX_WORKERS;
+struct PtrTable {
+    const void* p[kMaxBatch];
+};
+struct MutPtrTable {
+    void* p[kMaxBatch];
+};
+
 // Tile geometry shared by compress and decode.  Workgroup `blk` owns elements
 // [ebase, ebase + kTile) of bucket `bucket`, cut at `eend` (the bucket's end, the last
 // bucket's end being d rounded up to a multiple of 128 so the payload padding is covered).

@@ -10,16 +10,18 @@
 //
 // The density p on [-alpha, alpha] is the histogram's (constant inside a bin).  With the
 // prefix sums cum[i] = #{|g| below bin i} and H[i] = int_0^{lo_i} p^(1/3), both Q_U(alpha)
-// and the integral of p^(1/3) up to alpha cost O(1) per evaluation, so the fixed-point
-// iteration is a short scalar loop on lane 0; the per-bin cube roots and logarithms that
-// feed the prefix sums are computed by all lanes.
+// and the integral of p^(1/3) up to alpha cost O(1) per evaluation.  The per-bin cube roots
+// and logarithms and the two prefix sums are computed by all lanes (4 bins per lane, a
+// wavefront scan, a 4-entry carry through LDS); only the fixed-point iteration itself, a
+// chain of dependent scalar steps, runs on lane 0.
 #include "tq_device.h"
 
 namespace tq {
 
 constexpr int kNB = TQ_NBINS;
+constexpr int kBinsPerLane = 4;                           // 256 lanes x 4 >= 898 bins
 constexpr double kGammaFloor = 2.02;
-constexpr double kAlphaFloor = 5.421010862427522e-20;   // 2^-64
+constexpr double kAlphaFloor = 5.421010862427522e-20;     // 2^-64
 constexpr int kMaxIter = 100;
 constexpr double kRelTol = 1e-10;
 
@@ -40,10 +42,10 @@ __device__ __forceinline__ double bin_hi(int i, double absmax)
 // Bin whose [lo, hi) holds x >= 0 (the last bin is closed above).
 __device__ __forceinline__ int bin_of(double x)
 {
-    if (x < 9.094947017729282e-13) return 0;             // 2^-40
+    if (x < 9.094947017729282e-13) return 0;              // 2^-40
     if (x >= 65536.0) return kNB - 1;
     const int ex = ilogb(x);
-    const double m = ldexp(x, -ex);                       // in [1, 2), exact
+    const double m = ldexp(x, -ex);                        // in [1, 2), exact
     return (ex + 40) * 16 + (int)((m - 1.0) * 16.0) + 1;
 }
 
@@ -52,31 +54,54 @@ struct ParamsLds {
     double cum[kNB + 1];   // cum[i] = sum of hist below bin i
     double p13[kNB];       // cube root of the two-sided density on the bin
     double H[kNB + 1];     // H[i] = int_0^{lo_i} p^(1/3)
-    double tl[kNB];        // hist * ln(bin's geometric mean / g_min) for the binned tail index
-    double g_min;
+    double carry[4];       // per-wavefront totals of the scan in flight
+    double total;
     int tail_bin;
 };
+
+// Exclusive prefix sum over the 1024 (lane, slot) values v[0..3] of all 256 lanes, in bin
+// order; returns each lane's offset and leaves the grand total in L.total.
+__device__ __forceinline__ double block_exclusive_scan(double local, ParamsLds& L)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    double incl = local;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double o = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += o;
+    }
+    __syncthreads();                                       // previous use of carry is over
+    if (lane == 63) L.carry[wave] = incl;
+    __syncthreads();
+    double base = 0.0;
+    for (int w = 0; w < wave; ++w) base += L.carry[w];
+    if (threadIdx.x == kBlock - 1) L.total = base + incl;
+    return base + incl - local;
+}
 
 struct DensityView {
     const ParamsLds& L;
     double n, absmax;
-    __device__ double covered(int j, double x) const
+    __device__ double covered(int j, double x, double& w) const
     {
-        const double lo = bin_lo(j), w = bin_hi(j, absmax) - lo;
+        const double lo = bin_lo(j);
+        w = bin_hi(j, absmax) - lo;
         double c = x - lo;
-        c = c < 0.0 ? 0.0 : (c > w ? w : c);
-        return c;
+        return c < 0.0 ? 0.0 : (c > w ? w : c);
     }
     __device__ double Q_U(double a) const
     {
         const int j = bin_of(a);
-        const double w = bin_hi(j, absmax) - bin_lo(j);
-        return (L.cum[j] + L.hist[j] * (covered(j, a) / w)) / n;
+        double w;
+        const double c = covered(j, a, w);
+        return (L.cum[j] + L.hist[j] * (c / w)) / n;
     }
     __device__ double half_int(double x) const            // int_0^x p^(1/3)
     {
         const int j = bin_of(x);
-        return L.H[j] + L.p13[j] * covered(j, x);
+        double w;
+        const double c = covered(j, x, w);
+        return L.H[j] + L.p13[j] * c;
     }
     __device__ double Q_N(double a) const
     {
@@ -95,77 +120,96 @@ struct DensityView {
     }
 };
 
-__global__ __launch_bounds__(kBlock) void tq_params_kernel(const tq_stats_t* __restrict__ stats, int bits,
-                                                           int grid, float alpha_override,
-                                                           tq_params_t* __restrict__ params)
+__global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_tab, int bits, int grid,
+                                                           float alpha_override, const MutPtrTable params_tab)
 {
     __shared__ ParamsLds L;
-    const tq_stats_t* S = stats + blockIdx.x;
+    // blockIdx.x = bucket, blockIdx.y = tensor of the batch
+    const tq_stats_t* S = static_cast<const tq_stats_t*>(stats_tab.p[blockIdx.y]) + blockIdx.x;
+    tq_params_t* params = static_cast<tq_params_t*>(params_tab.p[blockIdx.y]);
     const int tid = threadIdx.x;
+    const int i0 = tid * kBinsPerLane;
     const double absmax = (double)S->absmax;
+    const bool fixed_gmin = S->g_min > 0.0f;
 
-    for (int i = tid; i < kNB; i += kBlock) L.hist[i] = (double)S->hist[i];
+    // counts and their prefix sums
+    double h[kBinsPerLane], local = 0.0;
+#pragma unroll
+    for (int k = 0; k < kBinsPerLane; ++k) {
+        h[k] = (i0 + k < kNB) ? (double)S->hist[i0 + k] : 0.0;
+        local += h[k];
+    }
+    double run = block_exclusive_scan(local, L);
+    if (tid == 0) L.tail_bin = kNB;
+    __syncthreads();
+    const double n = L.total;
+#pragma unroll
+    for (int k = 0; k < kBinsPerLane; ++k) {
+        if (i0 + k < kNB) { L.hist[i0 + k] = h[k]; L.cum[i0 + k] = run; }
+        run += h[k];
+        // Without a caller-fixed g_min the tail starts at the lower edge of the first bin at
+        // which the cumulative count reaches the 0.9-quantile of |g|.
+        if (i0 + k < kNB && n > 0.0 && 10.0 * run >= 9.0 * n) atomicMin(&L.tail_bin, i0 + k);
+    }
+    if (tid == kBlock - 1) L.cum[kNB] = n;
     __syncthreads();
 
-    if (tid == 0) {
-        double c = 0.0;
-        for (int i = 0; i < kNB; ++i) { L.cum[i] = c; c += L.hist[i]; }
-        L.cum[kNB] = c;
-        // Without a caller-fixed g_min the tail starts at the lower edge of the bin that
-        // holds the 0.9-quantile of |g|.
-        int tb = 0;
-        double gm = 0.0;
-        if (S->g_min > 0.0f) {
-            gm = (double)S->g_min;
-        } else if (c > 0.0) {
-            tb = kNB - 1;
-            for (int i = 0; i < kNB; ++i)
-                if (10.0 * L.cum[i + 1] >= 9.0 * c) { tb = i; break; }
-            gm = bin_lo(tb);                               // 0 when the quantile sits in bin 0
+    int tail_bin = L.tail_bin;
+    double g_min;
+    if (fixed_gmin) { g_min = (double)S->g_min; tail_bin = kNB; }
+    else if (tail_bin >= kNB) { g_min = 0.0; }
+    else g_min = bin_lo(tail_bin);                         // 0 when the quantile sits in bin 0
+    const bool binned_tail = !fixed_gmin && g_min > 0.0;
+
+    // density^(1/3), its integral up to each bin, and the binned log-sum of the tail
+    double pw[kBinsPerLane], local_h = 0.0, local_t = 0.0;
+#pragma unroll
+    for (int k = 0; k < kBinsPerLane; ++k) {
+        const int i = i0 + k;
+        pw[k] = 0.0;
+        if (i < kNB) {
+            const double lo = bin_lo(i), hi = bin_hi(i, absmax);
+            const double dens = n > 0.0 ? h[k] / (2.0 * n * (hi - lo)) : 0.0;
+            const double c = cbrt(dens);
+            L.p13[i] = c;
+            pw[k] = c * (hi - lo);
+            if (binned_tail && i >= tail_bin && h[k] > 0.0) {
+                const double rep = i < kNB - 1 ? sqrt(lo * hi) : lo;
+                local_t += h[k] * log(rep / g_min);
+            }
         }
-        L.tail_bin = tb;
-        L.g_min = gm;
+        local_h += pw[k];
+    }
+    double runh = block_exclusive_scan(local_h, L);
+#pragma unroll
+    for (int k = 0; k < kBinsPerLane; ++k) {
+        if (i0 + k < kNB) L.H[i0 + k] = runh;
+        runh += pw[k];
     }
     __syncthreads();
-
-    const double n = L.cum[kNB];
-    const bool binned_tail = !(S->g_min > 0.0f) && L.g_min > 0.0;
-    for (int i = tid; i < kNB; i += kBlock) {
-        const double lo = bin_lo(i), hi = bin_hi(i, absmax);
-        const double dens = n > 0.0 ? L.hist[i] / (2.0 * n * (hi - lo)) : 0.0;
-        L.p13[i] = cbrt(dens);
-        double t = 0.0;
-        if (binned_tail && i >= L.tail_bin && L.hist[i] > 0.0) {
-            const double rep = i < kNB - 1 ? sqrt(lo * hi) : lo;
-            t = L.hist[i] * log(rep / L.g_min);
-        }
-        L.tl[i] = t;
-    }
+    if (tid == kBlock - 1) L.H[kNB] = L.total;
+    const double excl_t = block_exclusive_scan(local_t, L);
+    (void)excl_t;
     __syncthreads();
+    const double sum_log_binned = L.total;
     if (tid != 0) return;
 
-    double h = 0.0;
-    for (int i = 0; i < kNB; ++i) { L.H[i] = h; h += L.p13[i] * (bin_hi(i, absmax) - bin_lo(i)); }
-    L.H[kNB] = h;
     const DensityView D{L, n, absmax};
-
     const int s = (1 << bits) - 1;
     uint32_t flags = 0;
-    double g_min = 0.0, gamma = 0.0, rho = 0.0, alpha;
+    double gamma = 0.0, rho = 0.0, alpha;
     if (n <= 0.0 || absmax <= 0.0) {
         flags |= TQ_F_DEGENERATE;
         alpha = kAlphaFloor;
+        g_min = 0.0;
     } else {
         double n_tail, sum_log;
-        g_min = L.g_min;
-        if (S->g_min > 0.0f) {
+        if (fixed_gmin) {
             n_tail = (double)S->n_tail;
             sum_log = S->sum_log_tail;
         } else {
-            n_tail = g_min > 0.0 ? n - L.cum[L.tail_bin] : 0.0;
-            sum_log = 0.0;
-            for (int i = L.tail_bin; i < kNB; ++i) sum_log += L.tl[i];
-            if (!(g_min > 0.0)) sum_log = 0.0;
+            n_tail = g_min > 0.0 ? n - L.cum[tail_bin] : 0.0;
+            sum_log = g_min > 0.0 ? sum_log_binned : 0.0;
         }
         const bool tail_ok = g_min > 0.0 && n_tail > 0.0 && sum_log > 0.0 && g_min < absmax;
         if (tail_ok) {
@@ -184,12 +228,14 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const tq_stats_t* __r
             const double a_min = g_min * (1.0 + 0.0009765625), a_max = absmax;
             const double C = 2.0 * rho * (double)(s * s) / (gu - 2.0);
             const double ex = 1.0 / (gu - 1.0);
+            const double log_c = log(C);
             auto clampa = [&](double a) { a = a > a_min ? a : a_min; return a < a_max ? a : a_max; };
-            double a = clampa(g_min * pow(C, ex));         // alpha' of Sec. IV-A (Q = 1)
+            double a = clampa(g_min * exp(ex * log_c));    // alpha' of Sec. IV-A (Q = 1)
             bool converged = false;
             for (int it = 0; it < kMaxIter; ++it) {
                 const double q = grid == TQ_GRID_UNIFORM ? D.Q_U(a) : D.Q_N(a);
-                const double an = q > 0.0 ? clampa(g_min * pow(C / q, ex)) : a_max;
+                // (C/q)^ex evaluated as exp(ex (ln C - ln q))
+                const double an = q > 0.0 ? clampa(g_min * exp(ex * (log_c - log(q)))) : a_max;
                 const bool done = fabs(an - a) <= kRelTol * an;
                 a = an;
                 if (done) { converged = true; break; }
@@ -248,12 +294,15 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const tq_stats_t* __r
 
 }  // namespace tq
 
-// Host side of tq_params after the argument checks of the C entry point.
-hipError_t tq_launch_params(const tq_stats_t* stats, uint64_t nb, int bits, int grid, float alpha_override,
-                            tq_params_t* params, hipStream_t st)
+// Host side of tq_params / tq_params_multi after the argument checks of the C entry points.
+hipError_t tq_launch_params(const tq_stats_t* const* stats, int count, uint64_t nb, int bits, int grid,
+                            float alpha_override, tq_params_t* const* params, hipStream_t st)
 {
-    if (nb == 0 || nb > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(tq::tq_params_kernel, dim3((unsigned)nb), dim3(tq::kBlock), 0, st, stats, bits, grid,
-                       alpha_override, params);
+    if (nb == 0 || nb > 0x7FFFFFFFull || count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
+    tq::PtrTable stt{};
+    tq::MutPtrTable pt{};
+    for (int i = 0; i < count; ++i) { stt.p[i] = stats[i]; pt.p[i] = params[i]; }
+    hipLaunchKernelGGL(tq::tq_params_kernel, dim3((unsigned)nb, (unsigned)count), dim3(tq::kBlock), 0, st, stt, bits,
+                       grid, alpha_override, pt);
     return hipGetLastError();
 }

@@ -4,32 +4,39 @@
 // caller-fixed g_min, the two terms of the tail-index estimator of Sec. V,
 //   gamma = 1 + n_tail / sum_j ln(|g_j| / g_min).
 //
-// One read pass.  Each workgroup histograms a chunk of one bucket into replicated LDS
-// histograms (heavy-tailed data puts most lanes into a handful of bins; replicas spread the
-// same-address atomics) and merges the non-empty bins into the caller's record with integer
-// atomics, so the counts do not depend on scheduling.
+// Two launches, no atomics on global memory (same-address atomics from many workgroups
+// serialise at about 0.14 us each on this part):
+//   1. tq_stats_partial_kernel: each workgroup reads one contiguous slice of one bucket
+//      once, histograms it into replicated LDS histograms (heavy-tailed data puts most lanes
+//      into a handful of bins; replicas spread the same-address LDS atomics) and writes its
+//      partial counts to the caller's workspace, bin-major: ws[bucket][bin][slice].
+//   2. tq_stats_reduce_kernel: one wavefront per (bucket, bin) adds the slices' counts with
+//      coalesced loads; one more wavefront per bucket combines max, counts and the log-sum.
+// Counts are integers, so the result does not depend on scheduling; the log-sum is added
+// in a fixed order as well.
 #include "tq_device.h"
 
 namespace tq {
 
+constexpr int kStatsBlock = 512;                       // threads per workgroup of the partial kernel
+constexpr int kStatsTile = kStatsBlock * kGroup;       // elements per workgroup pass (4096)
 constexpr int kStatsReplicas = 8;
-constexpr int kStatsStride = 929;            // >= TQ_NBINS and = 1 mod 32: replicas fall in different banks
-constexpr int kStatsChunk = 8 * kTile;       // elements per workgroup (16384)
-constexpr int kBinBias = 1391;               // 16 * (biased exponent of 2^-40) - 1
+constexpr int kStatsStride = 929;                      // >= TQ_NBINS and = 1 mod 32: replicas in different banks
+constexpr int kStatsMinSlice = 4 * kStatsTile;         // smallest slice worth a workgroup (16384 elements)
+constexpr int kStatsMaxSlices = 1024;                  // slices per bucket at most (a lane adds 16 of them)
+constexpr int kStatsTargetGroups = 1024;               // workgroups aimed at when there are many buckets
+constexpr int kBinBias = 1391;                         // 16 * (biased exponent of 2^-40) - 1
 
-__global__ __launch_bounds__(kBlock) void tq_stats_init_kernel(tq_stats_t* stats, uint64_t d,
-                                                               uint64_t bucket_elems, float g_min)
+struct StatsExtra {            // per (bucket, slice), 24 bytes
+    uint32_t absmax_bits;
+    uint32_t n_nonfinite;
+    unsigned long long n_tail;
+    double sum_log;
+};
+
+__host__ __device__ inline uint64_t stats_ws_hist_words(uint64_t nb, uint32_t slices)
 {
-    tq_stats_t* S = stats + blockIdx.x;
-    uint32_t* w = reinterpret_cast<uint32_t*>(S);
-    for (uint32_t i = threadIdx.x; i < sizeof(tq_stats_t) / 4; i += kBlock) w[i] = 0u;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint64_t lo = (uint64_t)blockIdx.x * bucket_elems;
-        const uint64_t hi = lo + bucket_elems < d ? lo + bucket_elems : d;
-        S->n = hi - lo;
-        S->g_min = g_min > 0.0f ? g_min : 0.0f;
-    }
+    return nb * TQ_NBINS * (uint64_t)slices;
 }
 
 template <typename T>
@@ -51,20 +58,45 @@ __device__ __forceinline__ uint32_t wave_reduce_max(uint32_t v)
 }
 
 template <int DTYPE>
-__global__ __launch_bounds__(kBlock) void tq_stats_kernel(const void* __restrict__ g, uint64_t d,
-                                                          uint64_t bucket_elems, uint32_t chunks_per_bucket,
-                                                          float g_min, tq_stats_t* __restrict__ stats)
+__device__ __forceinline__ void load_bits(const void* g, uint64_t e0, uint32_t (&bits)[8])
 {
+    if constexpr (DTYPE == TQ_F32) {
+        const uint4* p = reinterpret_cast<const uint4*>(static_cast<const float*>(g) + e0);
+        const uint4 a = p[0], b = p[1];
+        bits[0] = a.x; bits[1] = a.y; bits[2] = a.z; bits[3] = a.w;
+        bits[4] = b.x; bits[5] = b.y; bits[6] = b.z; bits[7] = b.w;
+    } else {
+        const uint4 v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(g) + e0);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { bits[2 * i] = w[i] << 16; bits[2 * i + 1] = w[i] & 0xFFFF0000u; }
+    }
+}
+
+template <int DTYPE>
+__global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
+    const PtrTable g_tab, uint64_t d, uint64_t bucket_elems, uint32_t slices, uint64_t slice_elems,
+    float g_min, char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes)
+{
+    // blockIdx.y = tensor of the batch; each tensor has its own region of the workspace
+    const void* __restrict__ g = g_tab.p[blockIdx.y];
+    char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
+    uint32_t* __restrict__ ws_hist = reinterpret_cast<uint32_t*>(my_ws);
+    StatsExtra* __restrict__ ws_extra = reinterpret_cast<StatsExtra*>(my_ws + ws_hist_bytes);
     __shared__ uint32_t hist[kStatsReplicas * kStatsStride];
-    for (int i = threadIdx.x; i < kStatsReplicas * kStatsStride; i += kBlock) hist[i] = 0u;
+    __shared__ uint32_t red_u32[2][kStatsBlock / 64];
+    __shared__ unsigned long long red_u64[kStatsBlock / 64];
+    __shared__ double red_f64[kStatsBlock / 64];
+    for (int i = threadIdx.x; i < kStatsReplicas * kStatsStride; i += kStatsBlock) hist[i] = 0u;
     __syncthreads();
 
-    const uint32_t bucket = blockIdx.x / chunks_per_bucket;
-    const uint32_t chunk = blockIdx.x - bucket * chunks_per_bucket;
+    const uint32_t bucket = blockIdx.x / slices;
+    const uint32_t slice = blockIdx.x - bucket * slices;
     const uint64_t bstart = (uint64_t)bucket * bucket_elems;
     const uint64_t bend = bstart + bucket_elems < d ? bstart + bucket_elems : d;
-    const uint64_t cstart = bstart + (uint64_t)chunk * kStatsChunk;
-    const uint64_t cend = cstart + kStatsChunk < bend ? cstart + kStatsChunk : bend;
+    uint64_t cstart = bstart + (uint64_t)slice * slice_elems;
+    cstart = cstart < bend ? cstart : bend;
+    const uint64_t cend = cstart + slice_elems < bend ? cstart + slice_elems : bend;
 
     uint32_t* my_hist = hist + (threadIdx.x & (kStatsReplicas - 1)) * kStatsStride;
     const bool want_tail = g_min > 0.0f;
@@ -73,7 +105,7 @@ __global__ __launch_bounds__(kBlock) void tq_stats_kernel(const void* __restrict
     int32_t exp_sum = 0;          // sum of unbiased exponents of the tail elements
     double log2m_sum = 0.0;       // sum of log2(mantissa in [1,2)) of the tail elements
 
-    // One finite-or-not magnitude into the lane's running statistics.
+    // One magnitude into the lane's running statistics.
     auto take = [&](uint32_t raw) {
         const uint32_t a = raw & 0x7FFFFFFFu;                          // |g| as an ordered integer
         if (a >= 0x7F800000u) { ++nonfinite; return; }                 // Inf or NaN
@@ -88,22 +120,23 @@ __global__ __launch_bounds__(kBlock) void tq_stats_kernel(const void* __restrict
         }
     };
 
-    for (uint64_t e0 = cstart + (uint64_t)threadIdx.x * kGroup; e0 < cend; e0 += kTile) {
+    uint64_t e0 = cstart + (uint64_t)threadIdx.x * kGroup;
+    // two tiles per trip: four 16-byte loads in flight per lane
+    for (; e0 + kStatsTile + kGroup <= cend; e0 += 2 * kStatsTile) {
+        uint32_t b0[8], b1[8];
+        load_bits<DTYPE>(g, e0, b0);
+        load_bits<DTYPE>(g, e0 + kStatsTile, b1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) take(b0[j]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) take(b1[j]);
+    }
+    for (; e0 < cend; e0 += kStatsTile) {
         if (e0 + kGroup <= cend) {
-            uint32_t bits[8];
-            if constexpr (DTYPE == TQ_F32) {
-                const uint4* p = reinterpret_cast<const uint4*>(static_cast<const float*>(g) + e0);
-                const uint4 a = p[0], b = p[1];
-                bits[0] = a.x; bits[1] = a.y; bits[2] = a.z; bits[3] = a.w;
-                bits[4] = b.x; bits[5] = b.y; bits[6] = b.z; bits[7] = b.w;
-            } else {
-                const uint4 v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(g) + e0);
-                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            uint32_t b0[8];
+            load_bits<DTYPE>(g, e0, b0);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { bits[2 * i] = w[i] << 16; bits[2 * i + 1] = w[i] & 0xFFFF0000u; }
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) take(bits[j]);
+            for (int j = 0; j < 8; ++j) take(b0[j]);
         } else {                                                       // ragged end of the tensor
             for (uint64_t e = e0; e < cend; ++e) {
                 if constexpr (DTYPE == TQ_F32) take(static_cast<const uint32_t*>(g)[e]);
@@ -113,52 +146,202 @@ __global__ __launch_bounds__(kBlock) void tq_stats_kernel(const void* __restrict
     }
     __syncthreads();
 
-    tq_stats_t* S = stats + bucket;
-    for (int b = threadIdx.x; b < TQ_NBINS; b += kBlock) {
+    // partial counts of this slice, every bin (the workspace is not pre-cleared)
+    uint32_t* col = ws_hist + (uint64_t)bucket * TQ_NBINS * slices + slice;
+    for (int b = threadIdx.x; b < TQ_NBINS; b += kStatsBlock) {
         uint32_t total = 0u;
 #pragma unroll
         for (int r = 0; r < kStatsReplicas; ++r) total += hist[r * kStatsStride + b];
-        if (total) atomicAdd(&S->hist[b], total);
+        col[(uint64_t)b * slices] = total;
     }
 
+    // max, counts and log-sum of this slice: wavefront reduction, then lane 0 adds the 8 waves
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     amax_bits = wave_reduce_max(amax_bits);
     nonfinite = wave_reduce_add(nonfinite);
-    if ((threadIdx.x & 63) == 0) {
-        if (amax_bits) atomicMax(reinterpret_cast<uint32_t*>(&S->absmax), amax_bits);  // non-negative floats order as integers
-        if (nonfinite) atomicAdd(&S->n_nonfinite, nonfinite);
-    }
-    if (want_tail) {
-        n_tail = wave_reduce_add(n_tail);
-        // ln(a / g_min) = ln2 * (exponent + log2 mantissa) - ln g_min, summed per wavefront
-        double part = (double)exp_sum + log2m_sum;
-        part = wave_reduce_add(part);
-        if ((threadIdx.x & 63) == 0 && n_tail) {
-            const double sum_log = 0.6931471805599453 * part - (double)n_tail * log((double)g_min);
-            atomicAdd(reinterpret_cast<unsigned long long*>(&S->n_tail), (unsigned long long)n_tail);
-            atomicAdd(&S->sum_log_tail, sum_log);
+    const unsigned long long nt = wave_reduce_add((unsigned long long)n_tail);
+    const double part = wave_reduce_add((double)exp_sum + log2m_sum);
+    if (lane == 0) { red_u32[0][wave] = amax_bits; red_u32[1][wave] = nonfinite; red_u64[wave] = nt; red_f64[wave] = part; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        StatsExtra x{0u, 0u, 0ull, 0.0};
+        double p = 0.0;
+        for (int w = 0; w < kStatsBlock / 64; ++w) {
+            x.absmax_bits = red_u32[0][w] > x.absmax_bits ? red_u32[0][w] : x.absmax_bits;
+            x.n_nonfinite += red_u32[1][w];
+            x.n_tail += red_u64[w];
+            p += red_f64[w];
         }
+        // ln(a / g_min) = ln2 * (exponent + log2 mantissa) - ln g_min
+        if (x.n_tail) x.sum_log = 0.6931471805599453 * p - (double)x.n_tail * log((double)g_min);
+        ws_extra[(uint64_t)bucket * slices + slice] = x;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void tq_stats_reduce_kernel(
+    const char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes, uint32_t slices,
+    uint32_t groups_per_bucket, uint64_t d, uint64_t bucket_elems, float g_min, const MutPtrTable stats_tab)
+{
+    const char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
+    const uint32_t* __restrict__ ws_hist = reinterpret_cast<const uint32_t*>(my_ws);
+    const StatsExtra* __restrict__ ws_extra = reinterpret_cast<const StatsExtra*>(my_ws + ws_hist_bytes);
+    tq_stats_t* __restrict__ stats = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]);
+    const uint32_t bucket = blockIdx.x / groups_per_bucket;
+    const uint32_t grp = blockIdx.x - bucket * groups_per_bucket;
+    const int lane = threadIdx.x & 63;
+    const uint32_t item = grp * (kBlock / 64) + (threadIdx.x >> 6);    // one wavefront per bin, one for the rest
+    tq_stats_t* S = stats + bucket;
+    if (item < TQ_NBINS) {
+        const uint32_t* row = ws_hist + ((uint64_t)bucket * TQ_NBINS + item) * slices;
+        uint32_t total = 0u;
+        for (uint32_t p = lane; p < slices; p += 64) total += row[p];
+        total = wave_reduce_add(total);
+        if (lane == 0) S->hist[item] = total;
+    } else if (item == TQ_NBINS) {
+        const StatsExtra* row = ws_extra + (uint64_t)bucket * slices;
+        uint32_t amax = 0u, nonfinite = 0u;
+        unsigned long long n_tail = 0ull;
+        double sum_log = 0.0;
+        for (uint32_t p = lane; p < slices; p += 64) {
+            const StatsExtra x = row[p];
+            amax = x.absmax_bits > amax ? x.absmax_bits : amax;
+            nonfinite += x.n_nonfinite;
+            n_tail += x.n_tail;
+            sum_log += x.sum_log;
+        }
+        amax = wave_reduce_max(amax);
+        nonfinite = wave_reduce_add(nonfinite);
+        n_tail = wave_reduce_add(n_tail);
+        sum_log = wave_reduce_add(sum_log);
+        if (lane == 0) {
+            const uint64_t lo = (uint64_t)bucket * bucket_elems;
+            const uint64_t hi = lo + bucket_elems < d ? lo + bucket_elems : d;
+            S->n_nonfinite = nonfinite;
+            S->absmax = __uint_as_float(amax);         // non-negative floats order as integers
+            S->n = hi - lo;
+            S->g_min = g_min > 0.0f ? g_min : 0.0f;
+            S->reserved = 0u;
+            S->n_tail = n_tail;
+            S->sum_log_tail = sum_log;
+        }
+    }
+}
+
+// Same reduction when a bucket has few slices: one lane per bin (and one for the rest), so a
+// tensor cut into many buckets does not need a wavefront per (bucket, bin).
+__global__ __launch_bounds__(kBlock) void tq_stats_reduce_small_kernel(
+    const char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes, uint32_t slices,
+    uint32_t groups_per_bucket, uint64_t d, uint64_t bucket_elems, float g_min, const MutPtrTable stats_tab)
+{
+    const char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
+    const uint32_t* __restrict__ ws_hist = reinterpret_cast<const uint32_t*>(my_ws);
+    const StatsExtra* __restrict__ ws_extra = reinterpret_cast<const StatsExtra*>(my_ws + ws_hist_bytes);
+    tq_stats_t* __restrict__ stats = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]);
+    const uint32_t bucket = blockIdx.x / groups_per_bucket;
+    const uint32_t grp = blockIdx.x - bucket * groups_per_bucket;
+    const uint32_t item = grp * kBlock + threadIdx.x;
+    tq_stats_t* S = stats + bucket;
+    if (item < TQ_NBINS) {
+        const uint32_t* row = ws_hist + ((uint64_t)bucket * TQ_NBINS + item) * slices;
+        uint32_t total = 0u;
+        for (uint32_t p = 0; p < slices; ++p) total += row[p];
+        S->hist[item] = total;
+    } else if (item == TQ_NBINS) {
+        const StatsExtra* row = ws_extra + (uint64_t)bucket * slices;
+        uint32_t amax = 0u, nonfinite = 0u;
+        unsigned long long n_tail = 0ull;
+        double sum_log = 0.0;
+        for (uint32_t p = 0; p < slices; ++p) {
+            const StatsExtra x = row[p];
+            amax = x.absmax_bits > amax ? x.absmax_bits : amax;
+            nonfinite += x.n_nonfinite;
+            n_tail += x.n_tail;
+            sum_log += x.sum_log;
+        }
+        const uint64_t lo = (uint64_t)bucket * bucket_elems;
+        const uint64_t hi = lo + bucket_elems < d ? lo + bucket_elems : d;
+        S->n_nonfinite = nonfinite;
+        S->absmax = __uint_as_float(amax);
+        S->n = hi - lo;
+        S->g_min = g_min > 0.0f ? g_min : 0.0f;
+        S->reserved = 0u;
+        S->n_tail = n_tail;
+        S->sum_log_tail = sum_log;
     }
 }
 
 }  // namespace tq
 
-// Host side of tq_stats after the argument checks of the C entry point.
-hipError_t tq_launch_stats(const void* g, int dtype, uint64_t d, uint64_t bucket_elems, float g_min,
-                           tq_stats_t* stats, hipStream_t st)
+namespace {
+
+struct StatsPlan {
+    uint64_t be, nb, slice_elems;
+    uint32_t slices;
+};
+
+StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems)
 {
-    const uint64_t be = bucket_elems ? bucket_elems : d;
-    const uint64_t nb = (d + be - 1) / be;
-    const uint64_t cpb = (be + tq::kStatsChunk - 1) / tq::kStatsChunk;
-    const uint64_t nblocks = nb * cpb;
-    if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(tq::tq_stats_init_kernel, dim3((unsigned)nb), dim3(tq::kBlock), 0, st, stats, d, be, g_min);
+    StatsPlan p;
+    p.be = bucket_elems ? bucket_elems : d;
+    p.nb = (d + p.be - 1) / p.be;
+    uint64_t want = (p.be + tq::kStatsMinSlice - 1) / tq::kStatsMinSlice;   // slices of >= 16384 elements
+    uint64_t cap = tq::kStatsTargetGroups / p.nb;                             // about 1024 workgroups in all
+    cap = cap < 1 ? 1 : (cap > tq::kStatsMaxSlices ? tq::kStatsMaxSlices : cap);
+    p.slices = (uint32_t)(want < cap ? want : cap);
+    if (p.slices < 1) p.slices = 1;
+    const uint64_t per = (p.be + p.slices - 1) / p.slices;
+    p.slice_elems = (per + tq::kStatsTile - 1) / tq::kStatsTile * tq::kStatsTile;
+    return p;
+}
+
+}  // namespace
+
+uint64_t tq_stats_workspace_bytes_impl(uint64_t d, uint64_t bucket_elems)
+{
+    if (d == 0) return 0;
+    const StatsPlan p = plan_stats(d, bucket_elems);
+    const uint64_t hist_bytes = tq::stats_ws_hist_words(p.nb, p.slices) * 4;
+    const uint64_t bytes = (hist_bytes + 15) / 16 * 16 + p.nb * p.slices * sizeof(tq::StatsExtra);
+    return (bytes + 255) / 256 * 256;                                  // regions of a batch stay aligned
+}
+
+// Host side of tq_stats / tq_stats_multi after the argument checks of the C entry points:
+// `count` same-shaped tensors in one pair of launches (grid.y), each with its own region of
+// tq_stats_workspace_bytes(d, bucket_elems) bytes of the workspace.
+hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
+                           float g_min, tq_stats_t* const* stats, void* workspace, hipStream_t st)
+{
+    const StatsPlan p = plan_stats(d, bucket_elems);
+    const uint64_t nblocks = p.nb * p.slices;
+    if (nblocks == 0 || nblocks > 0x7FFFFFFFull || count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
+    const uint64_t hist_bytes = (tq::stats_ws_hist_words(p.nb, p.slices) * 4 + 15) / 16 * 16;
+    const uint64_t tensor_bytes = tq_stats_workspace_bytes_impl(d, bucket_elems);
+    tq::PtrTable gt{};
+    tq::MutPtrTable stt{};
+    for (int i = 0; i < count; ++i) { gt.p[i] = g[i]; stt.p[i] = stats[i]; }
+    char* ws = static_cast<char*>(workspace);
+    const dim3 pgrid((unsigned)nblocks, (unsigned)count);
+    if (dtype == TQ_F32)
+        hipLaunchKernelGGL((tq::tq_stats_partial_kernel<TQ_F32>), pgrid, dim3(tq::kStatsBlock), 0, st, gt, d, p.be,
+                           p.slices, p.slice_elems, g_min, ws, tensor_bytes, hist_bytes);
+    else
+        hipLaunchKernelGGL((tq::tq_stats_partial_kernel<TQ_BF16>), pgrid, dim3(tq::kStatsBlock), 0, st, gt, d, p.be,
+                           p.slices, p.slice_elems, g_min, ws, tensor_bytes, hist_bytes);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    if (dtype == TQ_F32)
-        hipLaunchKernelGGL((tq::tq_stats_kernel<TQ_F32>), dim3((unsigned)nblocks), dim3(tq::kBlock), 0, st, g, d, be,
-                           (uint32_t)cpb, g_min, stats);
-    else
-        hipLaunchKernelGGL((tq::tq_stats_kernel<TQ_BF16>), dim3((unsigned)nblocks), dim3(tq::kBlock), 0, st, g, d,
-                           be, (uint32_t)cpb, g_min, stats);
+    const uint32_t items = TQ_NBINS + 1;                               // bins + one item for the rest
+    if (p.slices <= 16) {
+        const uint32_t gpb = (items + tq::kBlock - 1) / tq::kBlock;     // one lane per item
+        const uint64_t rblocks = p.nb * gpb;
+        if (rblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(tq::tq_stats_reduce_small_kernel, dim3((unsigned)rblocks, (unsigned)count), dim3(tq::kBlock),
+                           0, st, ws, tensor_bytes, hist_bytes, p.slices, gpb, d, p.be, g_min, stt);
+    } else {
+        const uint32_t gpb = (items + tq::kBlock / 64 - 1) / (tq::kBlock / 64);   // one wavefront per item
+        const uint64_t rblocks = p.nb * gpb;
+        if (rblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(tq::tq_stats_reduce_kernel, dim3((unsigned)rblocks, (unsigned)count), dim3(tq::kBlock), 0,
+                           st, ws, tensor_bytes, hist_bytes, p.slices, gpb, d, p.be, g_min, stt);
+    }
     return hipGetLastError();
 }

@@ -26,8 +26,9 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
-    assert set(names) == {"tq_num_buckets", "tq_payload_bytes", "tq_stats", "tq_params",
-                          "tq_compress", "tq_decompress_aggregate", "tq_strerror"}
+    assert set(names) == {"tq_num_buckets", "tq_payload_bytes", "tq_stats", "tq_stats_workspace_bytes", "tq_params",
+                          "tq_compress", "tq_decompress_aggregate", "tq_strerror",
+                          "tq_stats_multi", "tq_params_multi", "tq_compress_multi"}
     for n in names:
         assert getattr(L, n) is not None
 
@@ -58,12 +59,14 @@ def test_bad_arguments_are_rejected_without_a_device(L):
     from paper_2402_01798_amd import binding as B
     p = C.c_void_p(0x1000)             # never dereferenced: every call below fails its checks
     odd = C.c_void_p(0x1004)
-    assert L.tq_stats(p, 0, 0, 0, 0.0, p, None) == B.EINVAL                  # d = 0
-    assert L.tq_stats(p, 7, 100, 0, 0.0, p, None) == B.EINVAL                # dtype
-    assert L.tq_stats(p, 0, 1000, 100, 0.0, p, None) == B.EINVAL             # bucket not multiple of 128
-    assert L.tq_stats(p, 0, 1000, 0, 1e-20, p, None) == B.EINVAL             # g_min below the histogram
-    assert L.tq_stats(odd, 0, 1000, 0, 0.0, p, None) == B.EALIGN
-    assert L.tq_stats(None, 0, 1000, 0, 0.0, p, None) == B.EINVAL
+    assert L.tq_stats(p, 0, 0, 0, 0.0, p, p, 1 << 30, None) == B.EINVAL        # d = 0
+    assert L.tq_stats(p, 7, 100, 0, 0.0, p, p, 1 << 30, None) == B.EINVAL      # dtype
+    assert L.tq_stats(p, 0, 1000, 100, 0.0, p, p, 1 << 30, None) == B.EINVAL   # bucket not multiple of 128
+    assert L.tq_stats(p, 0, 1000, 0, 1e-20, p, p, 1 << 30, None) == B.EINVAL   # g_min below the histogram
+    assert L.tq_stats(odd, 0, 1000, 0, 0.0, p, p, 1 << 30, None) == B.EALIGN
+    assert L.tq_stats(p, 0, 1000, 0, 0.0, p, p, 16, None) == B.EINVAL          # workspace too small
+    assert L.tq_stats(p, 0, 1000, 0, 0.0, p, None, 1 << 30, None) == B.EINVAL  # no workspace
+    assert L.tq_stats(None, 0, 1000, 0, 0.0, p, p, 1 << 30, None) == B.EINVAL
     assert L.tq_params(p, 1, 5, 0, 0.0, p, None) == B.EINVAL                 # bits
     assert L.tq_params(p, 1, 3, 2, 0.0, p, None) == B.EINVAL                 # grid
     assert L.tq_params(p, 0, 3, 0, 0.0, p, None) == B.EINVAL                 # no buckets

@@ -71,6 +71,16 @@ def test_weights_and_accumulate():
     assert (got == want).all()
 
 
+@pytest.mark.parametrize("bits,N", [(4, 32), (4, 25), (3, 64), (4, 7), (2, 13)])
+def test_many_workers_take_the_general_kernel_when_the_pair_tables_do_not_fit(bits, N):
+    d = 12_345
+    gs, Ps, pays = make_workers("cfg1", 3, d, bits, B.GRID_NONUNIFORM)
+    paysN, PsN = [pays[i % 3] for i in range(N)], [Ps[i % 3] for i in range(N)]
+    want = O.decompress_aggregate(paysN, PsN, d, bits)
+    got = device_decode(paysN, PsN, d, bits)
+    assert (got == want).all()
+
+
 def test_max_workers_and_beyond():
     d, bits = 5000, 2
     gs, Ps, pays = make_workers("cfg1", 2, d, bits, B.GRID_UNIFORM)

@@ -17,11 +17,12 @@ def run_device(wl, gs_dev, bits, grid, seed, step):
     d = gs_dev[0].numel()
     N = len(gs_dev)
     stats = [B.alloc_stats(d, wl.bucket_elems) for _ in range(N)]
+    ws = B.alloc_stats_workspace(d, wl.bucket_elems)      # shared: the calls are ordered on one stream
     params = [B.alloc_params(d, wl.bucket_elems) for _ in range(N)]
     pays = [B.alloc_payload(d, bits) for _ in range(N)]
     out = torch.empty(d, dtype=torch.float32, device="cuda")
     for i in range(N):
-        B.tq_stats(gs_dev[i], stats[i], wl.bucket_elems, wl.g_min)
+        B.tq_stats(gs_dev[i], stats[i], ws, wl.bucket_elems, wl.g_min)
         B.tq_params(stats[i], params[i], bits, grid)
         B.tq_compress(gs_dev[i], params[i], pays[i], bits, seed, i, step, wl.bucket_elems)
     B.tq_decompress_aggregate(pays, params, out, bits, wl.bucket_elems)

@@ -14,7 +14,9 @@ pytestmark = pytest.mark.gpu
 def device_stats(g_dev, bucket=0, g_min=0.0):
     st = B.alloc_stats(g_dev.numel(), bucket)
     st.fill_(0x5A)                                   # must be overwritten in full
-    B.tq_stats(g_dev, st, bucket, g_min)
+    ws = B.alloc_stats_workspace(g_dev.numel(), bucket)
+    ws.fill_(0xC3)                                   # need not be cleared by the caller
+    B.tq_stats(g_dev, st, ws, bucket, g_min)
     torch.cuda.synchronize()
     return st
 
