@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--launch", default="batched", choices=["batched", "per-worker", "streams"],
                     help="how the N simulated workers are launched (see Path.step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="profiling aid: only run device-to-device copies of 1 GiB, the known-size "
+                         "kernel that scales the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--kernel-only", default="", help="profiling aid: loop one entry point only "
                     "(stats|params|compress|decode)")
     return ap.parse_args()
@@ -199,6 +202,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if a.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(a.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_each_way": src.numel() * 4, "copies": a.steps}))
+        return
     wl = synth.WORKLOADS[a.workload]
     bits = a.bits or wl.bits[0]
     grid = a.grid if a.grid >= 0 else wl.grids[0]

@@ -5,12 +5,12 @@
 // them in worker order and writes 32 contiguous bytes of fp32 once.
 //
 // Two kernels share that shape:
-//   tq_decode_pair_kernel  the fast path: per worker a table indexed by TWO adjacent codes
-//                          (2^(2b) entries of float2), so one 8-byte LDS read serves two
-//                          elements; a workgroup owns four tiles and requests all their code
-//                          words before anything else.
-//   tq_decode_kernel       the general path (any N up to 64 at any b): one 4-byte LDS read
-//                          per code from the plain 16-entry tables.
+//   tq_decode_fast_kernel    the fast path (N <= 16; N <= 8 at b = 4): per worker a table
+//                            indexed by TWO adjacent codes (2^(2b) entries of float2), so one
+//                            8-byte LDS read serves two elements; a single memory round trip
+//                            per workgroup.
+//   tq_decode_kernel         the general path (any N up to 64 at any b): one 4-byte LDS read
+//                            per code from the plain 16-entry tables.
 #include <type_traits>
 
 #include "tq_device.h"
@@ -72,22 +72,26 @@ __device__ __forceinline__ void fill_level_rows(float* table, const DecodeArgs& 
     }
 }
 
-// The kernel is bound by how many bytes a wavefront keeps in flight per memory round trip,
-// not by arithmetic: a workgroup therefore owns T consecutive tiles and requests the code
-// words of all of them (U workers at a time, U a divisor of N so that no branch sits between
-// the loads) before it builds its tables; the round trip that fetches the levels overlaps
-// with the one that fetches the codes.  Nothing is stored before the last load has been
-// consumed: on this ISA loads and stores retire through one in-order counter, so a wave that
-// stored a tile and then waited for further loads would wait for its own stores to land.
-template <int BITS, int T, int U>
-__global__ __launch_bounds__(kBlock) void tq_decode_pair_kernel(
+// tq_decode_fast_kernel<BITS, U, T>: U = workers handled (N rounded up to 1, 2, 4, 8 or 16;
+// the rows of the missing workers are zero and their stream is worker 0's, so they add 0),
+// T = tiles per workgroup.
+//
+// One shot per workgroup, no loop over tiles: on this ISA loads and stores retire through ONE
+// in-order counter, so a wave that stores a tile and then waits for further loads also waits
+// for its stores to reach memory; a wave that ends after its stores waits for nothing.  What
+// is left on the critical path is one memory round trip, so the kernel is arranged to make it
+// exactly one: the code words of all T tiles are requested first; meanwhile each wavefront
+// fetches the level rows of "its" workers through a scalar (wave-uniform) pointer, expands
+// them to pair entries with two cross-lane reads and writes them to LDS; one barrier.
+template <int BITS, int U, int T>
+__global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     const DecodeArgs args, int N, int weighted, float scale, uint64_t d, uint64_t d_pad, uint64_t bucket_elems,
     uint32_t groups_per_bucket, int accumulate, uint64_t payload_bytes, float* __restrict__ out)
 {
     constexpr int PAIRS = 1 << (2 * BITS);
     constexpr uint32_t PMASK = PAIRS - 1;
-    extern __shared__ float2 pair_tab[];                       // [N][PAIRS]
-    __shared__ float rows[TQ_MAX_WORKERS * 16];
+    constexpr uint32_t CMASK = (1u << BITS) - 1u;
+    __shared__ float2 pair_tab[U * PAIRS];
 
     const uint32_t bucket = blockIdx.x / groups_per_bucket;
     const uint32_t grp = blockIdx.x - bucket * groups_per_bucket;
@@ -97,8 +101,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_pair_kernel(
     const uint64_t gstart = bstart + (uint64_t)grp * T * kTile;
     if (gstart >= bend) return;
 
-    // This lane's group in each of the T tiles.  Lanes past the end of the bucket read group 0
-    // of the payload (always present) and store nothing.
+    // this lane's group in each tile; lanes past the end read group 0 (always present)
     uint64_t e0[T], off[T];
     bool room[T];
 #pragma unroll
@@ -107,56 +110,60 @@ __global__ __launch_bounds__(kBlock) void tq_decode_pair_kernel(
         off[t] = e0[t] < bend ? (e0[t] >> 3) * (uint64_t)BITS : 0;
         room[t] = off[t] + 4 <= payload_bytes;
     }
-    auto request = [&](uint32_t (&w)[T][U], int c) {
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int t = 0; t < T; ++t) w[t][u] = load_codes<BITS>(args.payload[U * c + u] + off[t], room[t]);
-    };
-
     uint32_t w[T][U];
-    request(w, 0);                                             // in flight while the tables are built
-
-    fill_level_rows(rows, args, N, weighted, bucket);
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < N * PAIRS; idx += kBlock) {
-        const float* r = rows + (idx / PAIRS) * 16;
-        const int e = idx & PMASK;
-        pair_tab[idx] = make_float2(r[e & ((1 << BITS) - 1)], r[e >> BITS]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint8_t* stream = args.payload[u < N ? u : 0];
+#pragma unroll
+        for (int t = 0; t < T; ++t) w[t][u] = load_codes<BITS>(stream + off[t], room[t]);
     }
-    __syncthreads();
 
-    float acc[T][8];
+    // pair tables: wavefront `wave` expands workers wave, wave + 4, ...  The wave index is
+    // read into a scalar register so that the worker's pointer and weight are scalar loads.
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    float lrow[(U + 3) / 4];
 #pragma unroll
-    for (int t = 0; t < T; ++t)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[t][j] = 0.0f;
-
-    const int n_chunks = N / U;
-    for (int c = 0; c < n_chunks; ++c) {
-        if (c > 0) request(w, c);
-        const float2* row0 = pair_tab + U * c * PAIRS;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const float2* row = row0 + u * PAIRS;
-#pragma unroll
-            for (int t = 0; t < T; ++t)
-#pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    const float2 v = row[(w[t][u] >> (2 * BITS * m)) & PMASK];
-                    acc[t][2 * m] = acc[t][2 * m] + v.x;
-                    acc[t][2 * m + 1] = acc[t][2 * m + 1] + v.y;
-                }
+    for (int k = 0; k < (U + 3) / 4; ++k) {
+        const int i = wave + 4 * k;
+        lrow[k] = 0.0f;
+        if (i < N) {
+            const tq_params_t* P = args.params[i] + bucket;
+            const float wsel = weighted ? args.weight[i] : 1.0f;   // x * 1.0f is exact
+            lrow[k] = wsel * P->level[lane & 15];
         }
     }
+#pragma unroll
+    for (int k = 0; k < (U + 3) / 4; ++k) {
+        const int i = wave + 4 * k;
+        if (i < U) {
+#pragma unroll
+            for (int e = lane; e < PAIRS; e += 64) {
+                const float lo = __shfl(lrow[k], (int)(e & CMASK), 64);
+                const float hi = __shfl(lrow[k], (int)(e >> BITS), 64);
+                pair_tab[i * PAIRS + e] = make_float2(lo, hi);
+            }
+        }
+    }
+    __syncthreads();
+    const float post = weighted ? 1.0f : scale;                // x * 1.0f is exact
 
 #pragma unroll
     for (int t = 0; t < T; ++t) {
-        if (!weighted) {
+        float acc[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[t][j] = acc[t][j] * scale;
-        }
-        if (e0[t] < bend) store_group(out + e0[t], acc[t], e0[t], d, accumulate);
+        for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const float2 v = pair_tab[u * PAIRS + ((w[t][u] >> (2 * BITS * m)) & PMASK)];
+                acc[2 * m] = acc[2 * m] + v.x;
+                acc[2 * m + 1] = acc[2 * m + 1] + v.y;
+            }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = acc[j] * post;
+        if (e0[t] < bend) store_group(out + e0[t], acc, e0[t], d, accumulate);
     }
 }
 
@@ -217,31 +224,38 @@ hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const
     const int weighted = weights ? 1 : 0;
     const dim3 threads(tq::kBlock);
 
-    const size_t pair_lds = (size_t)N * (1u << (2 * bits)) * sizeof(float2);
-    if (pair_lds <= 48 * 1024) {
-        constexpr int T = 4;                                           // tiles per workgroup
+    if (N <= 16 && !(bits == 4 && N > 8)) {
+        constexpr int T = 2;                                           // tiles per workgroup
         const uint64_t gpb = (tpb + T - 1) / T;
         const uint64_t nblocks = nb * gpb;
         if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
         const dim3 blocks((unsigned)nblocks);
-        const int U = N % 8 == 0 ? 8 : (N % 4 == 0 ? 4 : (N % 2 == 0 ? 2 : 1));
-#define TQ_LAUNCH_PAIR(B, UU)                                                                             \
-    hipLaunchKernelGGL((tq::tq_decode_pair_kernel<B, T, UU>), blocks, threads, pair_lds, st, args, N, weighted, \
-                       scale, d, d_pad, be, (uint32_t)gpb, accumulate, pbytes, out)
-#define TQ_LAUNCH_PAIR_U(B)                  \
-    switch (U) {                             \
-        case 8: TQ_LAUNCH_PAIR(B, 8); break; \
-        case 4: TQ_LAUNCH_PAIR(B, 4); break; \
-        case 2: TQ_LAUNCH_PAIR(B, 2); break; \
-        default: TQ_LAUNCH_PAIR(B, 1); break; \
+        const int U = N <= 1 ? 1 : (N <= 2 ? 2 : (N <= 4 ? 4 : (N <= 8 ? 8 : 16)));
+#define TQ_LAUNCH_FAST(B, UU)                                                                               \
+    hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, T>), blocks, threads, 0, st, args, N, weighted, scale, \
+                       d, d_pad, be, (uint32_t)gpb, accumulate, pbytes, out)
+#define TQ_LAUNCH_FAST_U(B)                     \
+    switch (U) {                                \
+        case 1: TQ_LAUNCH_FAST(B, 1); break;    \
+        case 2: TQ_LAUNCH_FAST(B, 2); break;    \
+        case 4: TQ_LAUNCH_FAST(B, 4); break;    \
+        case 8: TQ_LAUNCH_FAST(B, 8); break;    \
+        default: TQ_LAUNCH_FAST(B, 16); break;  \
     }
         switch (bits) {
-            case 2: TQ_LAUNCH_PAIR_U(2) break;
-            case 3: TQ_LAUNCH_PAIR_U(3) break;
-            default: TQ_LAUNCH_PAIR_U(4) break;
+            case 2: TQ_LAUNCH_FAST_U(2) break;
+            case 3: TQ_LAUNCH_FAST_U(3) break;
+            default:
+                switch (U) {                    // 16 workers at b = 4 would need 32 KiB of tables
+                    case 1: TQ_LAUNCH_FAST(4, 1); break;
+                    case 2: TQ_LAUNCH_FAST(4, 2); break;
+                    case 4: TQ_LAUNCH_FAST(4, 4); break;
+                    default: TQ_LAUNCH_FAST(4, 8); break;
+                }
+                break;
         }
-#undef TQ_LAUNCH_PAIR_U
-#undef TQ_LAUNCH_PAIR
+#undef TQ_LAUNCH_FAST_U
+#undef TQ_LAUNCH_FAST
         return hipGetLastError();
     }
 

@@ -9,9 +9,11 @@
 //   1. tq_stats_partial_kernel: each workgroup reads one contiguous slice of one bucket
 //      once, histograms it into replicated LDS histograms (heavy-tailed data puts most lanes
 //      into a handful of bins; replicas spread the same-address LDS atomics) and writes its
-//      partial counts to the caller's workspace, bin-major: ws[bucket][bin][slice].
-//   2. tq_stats_reduce_kernel: one wavefront per (bucket, bin) adds the slices' counts with
-//      coalesced loads; one more wavefront per bucket combines max, counts and the log-sum.
+//      partial counts to the caller's workspace as one contiguous row: ws[bucket][slice][bin]
+//      (scattering them bin-major cost ten times their size in partial-line HBM writes).
+//   2. tq_stats_reduce_kernel: a workgroup per (bucket, 64 bins) adds the slices' rows, 16
+//      slices at a time, with coalesced loads; one more workgroup per bucket combines max,
+//      counts and the log-sum.
 // Counts are integers, so the result does not depend on scheduling; the log-sum is added
 // in a fixed order as well.
 #include "tq_device.h"
@@ -23,8 +25,10 @@ constexpr int kStatsTile = kStatsBlock * kGroup;       // elements per workgroup
 constexpr int kStatsReplicas = 8;
 constexpr int kStatsStride = 929;                      // >= TQ_NBINS and = 1 mod 32: replicas in different banks
 constexpr int kStatsMinSlice = 4 * kStatsTile;         // smallest slice worth a workgroup (16384 elements)
-constexpr int kStatsMaxSlices = 1024;                  // slices per bucket at most (a lane adds 16 of them)
-constexpr int kStatsTargetGroups = 1024;               // workgroups aimed at when there are many buckets
+constexpr int kStatsMaxSlices = 512;                   // slices per bucket at most
+constexpr int kStatsTargetGroups = 512;                // workgroups per tensor aimed at when there are many buckets
+constexpr int kReduceBlock = 1024;                     // threads of the reduce kernel: 64 bins x 16 slice lanes
+constexpr int kReduceBins = 64;
 constexpr int kBinBias = 1391;                         // 16 * (biased exponent of 2^-40) - 1
 
 struct StatsExtra {            // per (bucket, slice), 24 bytes
@@ -121,15 +125,15 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     };
 
     uint64_t e0 = cstart + (uint64_t)threadIdx.x * kGroup;
-    // two tiles per trip: four 16-byte loads in flight per lane
-    for (; e0 + kStatsTile + kGroup <= cend; e0 += 2 * kStatsTile) {
-        uint32_t b0[8], b1[8];
-        load_bits<DTYPE>(g, e0, b0);
-        load_bits<DTYPE>(g, e0 + kStatsTile, b1);
+    // four tiles per trip: eight 16-byte loads (fp32) in flight per lane
+    for (; e0 + 3 * (uint64_t)kStatsTile + kGroup <= cend; e0 += 4 * kStatsTile) {
+        uint32_t b[4][8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) take(b0[j]);
+        for (int t = 0; t < 4; ++t) load_bits<DTYPE>(g, e0 + (uint64_t)t * kStatsTile, b[t]);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) take(b1[j]);
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) take(b[t][j]);
     }
     for (; e0 < cend; e0 += kStatsTile) {
         if (e0 + kGroup <= cend) {
@@ -146,13 +150,14 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     }
     __syncthreads();
 
-    // partial counts of this slice, every bin (the workspace is not pre-cleared)
-    uint32_t* col = ws_hist + (uint64_t)bucket * TQ_NBINS * slices + slice;
+    // partial counts of this slice, every bin (the workspace is not pre-cleared), one
+    // contiguous row per workgroup
+    uint32_t* row = ws_hist + ((uint64_t)bucket * slices + slice) * TQ_NBINS;
     for (int b = threadIdx.x; b < TQ_NBINS; b += kStatsBlock) {
         uint32_t total = 0u;
 #pragma unroll
         for (int r = 0; r < kStatsReplicas; ++r) total += hist[r * kStatsStride + b];
-        col[(uint64_t)b * slices] = total;
+        row[b] = total;
     }
 
     // max, counts and log-sum of this slice: wavefront reduction, then lane 0 adds the 8 waves
@@ -178,26 +183,38 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     }
 }
 
-__global__ __launch_bounds__(kBlock) void tq_stats_reduce_kernel(
+__global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
     const char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes, uint32_t slices,
     uint32_t groups_per_bucket, uint64_t d, uint64_t bucket_elems, float g_min, const MutPtrTable stats_tab)
 {
+    __shared__ uint32_t part[kReduceBlock];
     const char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
     const uint32_t* __restrict__ ws_hist = reinterpret_cast<const uint32_t*>(my_ws);
     const StatsExtra* __restrict__ ws_extra = reinterpret_cast<const StatsExtra*>(my_ws + ws_hist_bytes);
     tq_stats_t* __restrict__ stats = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]);
     const uint32_t bucket = blockIdx.x / groups_per_bucket;
     const uint32_t grp = blockIdx.x - bucket * groups_per_bucket;
-    const int lane = threadIdx.x & 63;
-    const uint32_t item = grp * (kBlock / 64) + (threadIdx.x >> 6);    // one wavefront per bin, one for the rest
     tq_stats_t* S = stats + bucket;
-    if (item < TQ_NBINS) {
-        const uint32_t* row = ws_hist + ((uint64_t)bucket * TQ_NBINS + item) * slices;
+
+    if (grp + 1 < groups_per_bucket) {
+        // 64 consecutive bins x 16 interleaved slice lanes; a wavefront reads 256 contiguous bytes
+        const uint32_t bin = grp * kReduceBins + (threadIdx.x & (kReduceBins - 1));
+        const uint32_t sl = threadIdx.x / kReduceBins;
         uint32_t total = 0u;
-        for (uint32_t p = lane; p < slices; p += 64) total += row[p];
-        total = wave_reduce_add(total);
-        if (lane == 0) S->hist[item] = total;
-    } else if (item == TQ_NBINS) {
+        if (bin < TQ_NBINS) {
+            const uint32_t* col = ws_hist + (uint64_t)bucket * slices * TQ_NBINS + bin;
+            for (uint32_t p = sl; p < slices; p += kReduceBlock / kReduceBins) total += col[(uint64_t)p * TQ_NBINS];
+        }
+        part[threadIdx.x] = total;
+        __syncthreads();
+        if (threadIdx.x < kReduceBins && bin < TQ_NBINS) {
+#pragma unroll
+            for (int k = 1; k < kReduceBlock / kReduceBins; ++k) total += part[threadIdx.x + k * kReduceBins];
+            S->hist[bin] = total;
+        }
+    } else if (threadIdx.x < 64) {
+        // last workgroup of the bucket: max, counts and the log-sum of the slices (fixed order)
+        const int lane = threadIdx.x;
         const StatsExtra* row = ws_extra + (uint64_t)bucket * slices;
         uint32_t amax = 0u, nonfinite = 0u;
         unsigned long long n_tail = 0ull;
@@ -224,49 +241,6 @@ __global__ __launch_bounds__(kBlock) void tq_stats_reduce_kernel(
             S->n_tail = n_tail;
             S->sum_log_tail = sum_log;
         }
-    }
-}
-
-// Same reduction when a bucket has few slices: one lane per bin (and one for the rest), so a
-// tensor cut into many buckets does not need a wavefront per (bucket, bin).
-__global__ __launch_bounds__(kBlock) void tq_stats_reduce_small_kernel(
-    const char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes, uint32_t slices,
-    uint32_t groups_per_bucket, uint64_t d, uint64_t bucket_elems, float g_min, const MutPtrTable stats_tab)
-{
-    const char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
-    const uint32_t* __restrict__ ws_hist = reinterpret_cast<const uint32_t*>(my_ws);
-    const StatsExtra* __restrict__ ws_extra = reinterpret_cast<const StatsExtra*>(my_ws + ws_hist_bytes);
-    tq_stats_t* __restrict__ stats = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]);
-    const uint32_t bucket = blockIdx.x / groups_per_bucket;
-    const uint32_t grp = blockIdx.x - bucket * groups_per_bucket;
-    const uint32_t item = grp * kBlock + threadIdx.x;
-    tq_stats_t* S = stats + bucket;
-    if (item < TQ_NBINS) {
-        const uint32_t* row = ws_hist + ((uint64_t)bucket * TQ_NBINS + item) * slices;
-        uint32_t total = 0u;
-        for (uint32_t p = 0; p < slices; ++p) total += row[p];
-        S->hist[item] = total;
-    } else if (item == TQ_NBINS) {
-        const StatsExtra* row = ws_extra + (uint64_t)bucket * slices;
-        uint32_t amax = 0u, nonfinite = 0u;
-        unsigned long long n_tail = 0ull;
-        double sum_log = 0.0;
-        for (uint32_t p = 0; p < slices; ++p) {
-            const StatsExtra x = row[p];
-            amax = x.absmax_bits > amax ? x.absmax_bits : amax;
-            nonfinite += x.n_nonfinite;
-            n_tail += x.n_tail;
-            sum_log += x.sum_log;
-        }
-        const uint64_t lo = (uint64_t)bucket * bucket_elems;
-        const uint64_t hi = lo + bucket_elems < d ? lo + bucket_elems : d;
-        S->n_nonfinite = nonfinite;
-        S->absmax = __uint_as_float(amax);
-        S->n = hi - lo;
-        S->g_min = g_min > 0.0f ? g_min : 0.0f;
-        S->reserved = 0u;
-        S->n_tail = n_tail;
-        S->sum_log_tail = sum_log;
     }
 }
 
@@ -329,19 +303,11 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
                            p.slices, p.slice_elems, g_min, ws, tensor_bytes, hist_bytes);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    const uint32_t items = TQ_NBINS + 1;                               // bins + one item for the rest
-    if (p.slices <= 16) {
-        const uint32_t gpb = (items + tq::kBlock - 1) / tq::kBlock;     // one lane per item
-        const uint64_t rblocks = p.nb * gpb;
-        if (rblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(tq::tq_stats_reduce_small_kernel, dim3((unsigned)rblocks, (unsigned)count), dim3(tq::kBlock),
-                           0, st, ws, tensor_bytes, hist_bytes, p.slices, gpb, d, p.be, g_min, stt);
-    } else {
-        const uint32_t gpb = (items + tq::kBlock / 64 - 1) / (tq::kBlock / 64);   // one wavefront per item
-        const uint64_t rblocks = p.nb * gpb;
-        if (rblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(tq::tq_stats_reduce_kernel, dim3((unsigned)rblocks, (unsigned)count), dim3(tq::kBlock), 0,
-                           st, ws, tensor_bytes, hist_bytes, p.slices, gpb, d, p.be, g_min, stt);
-    }
+    // one workgroup per 64 bins, plus one per bucket for the scalar fields
+    const uint32_t gpb = (TQ_NBINS + tq::kReduceBins - 1) / tq::kReduceBins + 1;
+    const uint64_t rblocks = p.nb * gpb;
+    if (rblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tq::tq_stats_reduce_kernel, dim3((unsigned)rblocks, (unsigned)count), dim3(tq::kReduceBlock), 0,
+                       st, ws, tensor_bytes, hist_bytes, p.slices, gpb, d, p.be, g_min, stt);
     return hipGetLastError();
 }
