@@ -25,17 +25,21 @@ constexpr int kStatsTile = kStatsBlock * kGroup;       // elements per workgroup
 constexpr int kStatsReplicas = 8;
 constexpr int kStatsStride = 929;                      // >= TQ_NBINS and = 1 mod 32: replicas in different banks
 constexpr int kStatsMinSlice = 4 * kStatsTile;         // smallest slice worth a workgroup (16384 elements)
-constexpr int kStatsMaxSlices = 512;                   // slices per bucket at most
-constexpr int kStatsTargetGroups = 512;                // workgroups per tensor aimed at when there are many buckets
+constexpr int kStatsMaxSlices = 256;                   // slices per bucket at most
+constexpr int kStatsTargetGroups = 256;                // workgroups aimed at in one launch (one per CU)
 constexpr int kReduceBlock = 1024;                     // threads of the reduce kernel: 64 bins x 16 slice lanes
 constexpr int kReduceBins = 64;
 constexpr int kBinBias = 1391;                         // 16 * (biased exponent of 2^-40) - 1
 
-struct StatsExtra {            // per (bucket, slice), 24 bytes
+// Per (bucket, slice).  The log-sum of the tail travels as two exact integer sums (ln(a/g_min)
+// = ln2 (exponent + log2 mantissa) - ln g_min, the log2 of the mantissa in 2^-32 fixed point),
+// so the final value does not depend on how the tensor was cut into slices or batched.
+struct StatsExtra {            // 32 bytes
     uint32_t absmax_bits;
     uint32_t n_nonfinite;
     unsigned long long n_tail;
-    double sum_log;
+    long long exp_sum;             // sum of unbiased exponents of the tail elements
+    unsigned long long log2m_fix;  // sum of log2(mantissa in [1,2)) * 2^32 of the tail elements
 };
 
 __host__ __device__ inline uint64_t stats_ws_hist_words(uint64_t nb, uint32_t slices)
@@ -77,7 +81,7 @@ __device__ __forceinline__ void load_bits(const void* g, uint64_t e0, uint32_t (
     }
 }
 
-template <int DTYPE>
+template <int DTYPE, bool TAIL>
 __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     const PtrTable g_tab, uint64_t d, uint64_t bucket_elems, uint32_t slices, uint64_t slice_elems,
     float g_min, char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes)
@@ -89,8 +93,7 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     StatsExtra* __restrict__ ws_extra = reinterpret_cast<StatsExtra*>(my_ws + ws_hist_bytes);
     __shared__ uint32_t hist[kStatsReplicas * kStatsStride];
     __shared__ uint32_t red_u32[2][kStatsBlock / 64];
-    __shared__ unsigned long long red_u64[kStatsBlock / 64];
-    __shared__ double red_f64[kStatsBlock / 64];
+    __shared__ unsigned long long red_u64[3][kStatsBlock / 64];
     for (int i = threadIdx.x; i < kStatsReplicas * kStatsStride; i += kStatsBlock) hist[i] = 0u;
     __syncthreads();
 
@@ -103,39 +106,71 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     const uint64_t cend = cstart + slice_elems < bend ? cstart + slice_elems : bend;
 
     uint32_t* my_hist = hist + (threadIdx.x & (kStatsReplicas - 1)) * kStatsStride;
-    const bool want_tail = g_min > 0.0f;
     const uint32_t gmin_bits = __float_as_uint(g_min);
     uint32_t amax_bits = 0u, nonfinite = 0u, n_tail = 0u;
-    int32_t exp_sum = 0;          // sum of unbiased exponents of the tail elements
-    double log2m_sum = 0.0;       // sum of log2(mantissa in [1,2)) of the tail elements
+    int32_t exp_sum = 0;                 // sum of unbiased exponents of the tail elements
+    unsigned long long log2m_fix = 0ull; // sum of log2(mantissa in [1,2)) in 2^-32 fixed point
 
-    // One magnitude into the lane's running statistics.
+    // One magnitude into the lane's running statistics.  Branch-free: NaN and Inf are counted
+    // into a spare slot behind the last bin of the lane's replica, so the loop body below is
+    // straight-line code and the next trip's loads can stay in flight across it.
     auto take = [&](uint32_t raw) {
         const uint32_t a = raw & 0x7FFFFFFFu;                          // |g| as an ordered integer
-        if (a >= 0x7F800000u) { ++nonfinite; return; }                 // Inf or NaN
+        const bool finite = a < 0x7F800000u;
         int32_t idx = (int32_t)(a >> 19) - kBinBias;
         idx = idx < 0 ? 0 : (idx > TQ_NBINS - 1 ? TQ_NBINS - 1 : idx);
+        idx = finite ? idx : TQ_NBINS;                                 // spare slot, never flushed
         atomicAdd(&my_hist[idx], 1u);
-        amax_bits = a > amax_bits ? a : amax_bits;
-        if (want_tail && a > gmin_bits) {                              // g_min >= 2^-40: a is normal
-            ++n_tail;
-            exp_sum += (int32_t)(a >> 23) - 127;
-            log2m_sum += (double)__log2f(__uint_as_float((a & 0x007FFFFFu) | 0x3F800000u));
+        nonfinite += finite ? 0u : 1u;
+        const uint32_t af = finite ? a : 0u;
+        amax_bits = af > amax_bits ? af : amax_bits;
+        if constexpr (TAIL) {                                          // g_min >= 2^-40: a tail value is normal
+            const bool in_tail = finite && a > gmin_bits;
+            n_tail += in_tail ? 1u : 0u;
+            exp_sum += in_tail ? (int32_t)(a >> 23) - 127 : 0;
+            const float l2 = __log2f(__uint_as_float((a & 0x007FFFFFu) | 0x3F800000u));   // in [0, 1]
+            const uint32_t fix = (uint32_t)(l2 * 4294967296.0f);       // saturating conversion
+            log2m_fix += in_tail ? fix : 0u;
         }
     };
 
-    uint64_t e0 = cstart + (uint64_t)threadIdx.x * kGroup;
-    // four tiles per trip: eight 16-byte loads (fp32) in flight per lane
-    for (; e0 + 3 * (uint64_t)kStatsTile + kGroup <= cend; e0 += 4 * kStatsTile) {
-        uint32_t b[4][8];
+    // Full trips of two tiles each, software-pipelined: the next trip's four 16-byte loads per
+    // lane are requested before the current trip's 16 values are histogrammed.  The trip count
+    // is the same for every lane of the workgroup; the rest of the slice follows tile by tile.
+    constexpr int kTrip = 2;
+    const uint64_t lane_e = cstart + (uint64_t)threadIdx.x * kGroup;
+    const uint32_t n_trips = (uint32_t)((cend - cstart) / ((uint64_t)kTrip * kStatsTile));
+    if (n_trips > 0) {
+        // two register buffers that swap roles (no copies: a copy would wait for the loads in
+        // flight); sched_barrier keeps each request ahead of the histogramming it overlaps
+        uint32_t bufA[kTrip][8], bufB[kTrip][8];
+        auto request = [&](uint32_t (&buf)[kTrip][8], uint32_t trip) {
+            trip = trip < n_trips ? trip : n_trips - 1;               // past the end: re-request the last trip
 #pragma unroll
-        for (int t = 0; t < 4; ++t) load_bits<DTYPE>(g, e0 + (uint64_t)t * kStatsTile, b[t]);
+            for (int t = 0; t < kTrip; ++t)
+                load_bits<DTYPE>(g, lane_e + ((uint64_t)trip * kTrip + t) * kStatsTile, buf[t]);
+        };
+        auto consume = [&](const uint32_t (&buf)[kTrip][8]) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < kTrip; ++t)
 #pragma unroll
-            for (int j = 0; j < 8; ++j) take(b[t][j]);
+                for (int j = 0; j < 8; ++j) take(buf[t][j]);
+        };
+        request(bufA, 0);
+        const uint32_t pairs = n_trips >> 1;
+        for (uint32_t p = 0; p < pairs; ++p) {
+            request(bufB, 2 * p + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(bufA);
+            __builtin_amdgcn_sched_barrier(0);
+            request(bufA, 2 * p + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(bufB);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (n_trips & 1u) consume(bufA);                               // holds trip n_trips - 1
     }
-    for (; e0 < cend; e0 += kStatsTile) {
+    for (uint64_t e0 = lane_e + (uint64_t)n_trips * kTrip * kStatsTile; e0 < cend; e0 += kStatsTile) {
         if (e0 + kGroup <= cend) {
             uint32_t b0[8];
             load_bits<DTYPE>(g, e0, b0);
@@ -165,20 +200,19 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     amax_bits = wave_reduce_max(amax_bits);
     nonfinite = wave_reduce_add(nonfinite);
     const unsigned long long nt = wave_reduce_add((unsigned long long)n_tail);
-    const double part = wave_reduce_add((double)exp_sum + log2m_sum);
-    if (lane == 0) { red_u32[0][wave] = amax_bits; red_u32[1][wave] = nonfinite; red_u64[wave] = nt; red_f64[wave] = part; }
+    const long long es = wave_reduce_add((long long)exp_sum);
+    const unsigned long long lf = wave_reduce_add(log2m_fix);
+    if (lane == 0) { red_u32[0][wave] = amax_bits; red_u32[1][wave] = nonfinite; red_u64[0][wave] = nt; red_u64[1][wave] = (unsigned long long)es; red_u64[2][wave] = lf; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        StatsExtra x{0u, 0u, 0ull, 0.0};
-        double p = 0.0;
+        StatsExtra x{0u, 0u, 0ull, 0ll, 0ull};
         for (int w = 0; w < kStatsBlock / 64; ++w) {
             x.absmax_bits = red_u32[0][w] > x.absmax_bits ? red_u32[0][w] : x.absmax_bits;
             x.n_nonfinite += red_u32[1][w];
-            x.n_tail += red_u64[w];
-            p += red_f64[w];
+            x.n_tail += red_u64[0][w];
+            x.exp_sum += (long long)red_u64[1][w];
+            x.log2m_fix += red_u64[2][w];
         }
-        // ln(a / g_min) = ln2 * (exponent + log2 mantissa) - ln g_min
-        if (x.n_tail) x.sum_log = 0.6931471805599453 * p - (double)x.n_tail * log((double)g_min);
         ws_extra[(uint64_t)bucket * slices + slice] = x;
     }
 }
@@ -217,19 +251,26 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
         const int lane = threadIdx.x;
         const StatsExtra* row = ws_extra + (uint64_t)bucket * slices;
         uint32_t amax = 0u, nonfinite = 0u;
-        unsigned long long n_tail = 0ull;
-        double sum_log = 0.0;
+        unsigned long long n_tail = 0ull, log2m_fix = 0ull;
+        long long exp_sum = 0ll;
         for (uint32_t p = lane; p < slices; p += 64) {
             const StatsExtra x = row[p];
             amax = x.absmax_bits > amax ? x.absmax_bits : amax;
             nonfinite += x.n_nonfinite;
             n_tail += x.n_tail;
-            sum_log += x.sum_log;
+            exp_sum += x.exp_sum;
+            log2m_fix += x.log2m_fix;
         }
         amax = wave_reduce_max(amax);
         nonfinite = wave_reduce_add(nonfinite);
         n_tail = wave_reduce_add(n_tail);
-        sum_log = wave_reduce_add(sum_log);
+        exp_sum = wave_reduce_add(exp_sum);
+        log2m_fix = wave_reduce_add(log2m_fix);
+        // ln(a / g_min) = ln2 * (exponent + log2 mantissa) - ln g_min, from exact integer sums
+        double sum_log = 0.0;
+        if (n_tail)
+            sum_log = 0.6931471805599453 * ((double)exp_sum + (double)log2m_fix * 2.3283064365386963e-10) -
+                      (double)n_tail * log((double)g_min);
         if (lane == 0) {
             const uint64_t lo = (uint64_t)bucket * bucket_elems;
             const uint64_t hi = lo + bucket_elems < d ? lo + bucket_elems : d;
@@ -253,13 +294,18 @@ struct StatsPlan {
     uint32_t slices;
 };
 
-StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems)
+// Slices per bucket.  Measured on MI355X: the partial kernel is fastest with about one
+// 512-thread workgroup per compute unit in the whole launch (each workgroup pays for clearing
+// and flushing its LDS histograms, so fewer, longer-lived workgroups win as long as every CU
+// has one), i.e. about 256 workgroups over all tensors and buckets of the batch.
+StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems, int count)
 {
     StatsPlan p;
     p.be = bucket_elems ? bucket_elems : d;
     p.nb = (d + p.be - 1) / p.be;
     uint64_t want = (p.be + tq::kStatsMinSlice - 1) / tq::kStatsMinSlice;   // slices of >= 16384 elements
-    uint64_t cap = tq::kStatsTargetGroups / p.nb;                             // about 1024 workgroups in all
+    const uint64_t units = p.nb * (uint64_t)(count < 1 ? 1 : count);
+    uint64_t cap = (tq::kStatsTargetGroups + units - 1) / units;
     cap = cap < 1 ? 1 : (cap > tq::kStatsMaxSlices ? tq::kStatsMaxSlices : cap);
     p.slices = (uint32_t)(want < cap ? want : cap);
     if (p.slices < 1) p.slices = 1;
@@ -273,7 +319,7 @@ StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems)
 uint64_t tq_stats_workspace_bytes_impl(uint64_t d, uint64_t bucket_elems)
 {
     if (d == 0) return 0;
-    const StatsPlan p = plan_stats(d, bucket_elems);
+    const StatsPlan p = plan_stats(d, bucket_elems, 1);                // a batch never uses more slices
     const uint64_t hist_bytes = tq::stats_ws_hist_words(p.nb, p.slices) * 4;
     const uint64_t bytes = (hist_bytes + 15) / 16 * 16 + p.nb * p.slices * sizeof(tq::StatsExtra);
     return (bytes + 255) / 256 * 256;                                  // regions of a batch stay aligned
@@ -285,7 +331,7 @@ uint64_t tq_stats_workspace_bytes_impl(uint64_t d, uint64_t bucket_elems)
 hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
                            float g_min, tq_stats_t* const* stats, void* workspace, hipStream_t st)
 {
-    const StatsPlan p = plan_stats(d, bucket_elems);
+    const StatsPlan p = plan_stats(d, bucket_elems, count);
     const uint64_t nblocks = p.nb * p.slices;
     if (nblocks == 0 || nblocks > 0x7FFFFFFFull || count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
     const uint64_t hist_bytes = (tq::stats_ws_hist_words(p.nb, p.slices) * 4 + 15) / 16 * 16;
@@ -295,12 +341,15 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
     for (int i = 0; i < count; ++i) { gt.p[i] = g[i]; stt.p[i] = stats[i]; }
     char* ws = static_cast<char*>(workspace);
     const dim3 pgrid((unsigned)nblocks, (unsigned)count);
-    if (dtype == TQ_F32)
-        hipLaunchKernelGGL((tq::tq_stats_partial_kernel<TQ_F32>), pgrid, dim3(tq::kStatsBlock), 0, st, gt, d, p.be,
-                           p.slices, p.slice_elems, g_min, ws, tensor_bytes, hist_bytes);
-    else
-        hipLaunchKernelGGL((tq::tq_stats_partial_kernel<TQ_BF16>), pgrid, dim3(tq::kStatsBlock), 0, st, gt, d, p.be,
-                           p.slices, p.slice_elems, g_min, ws, tensor_bytes, hist_bytes);
+#define TQ_LAUNCH_PARTIAL(DT, TL)                                                                             \
+    hipLaunchKernelGGL((tq::tq_stats_partial_kernel<DT, TL>), pgrid, dim3(tq::kStatsBlock), 0, st, gt, d, p.be,   \
+                       p.slices, p.slice_elems, g_min, ws, tensor_bytes, hist_bytes)
+    if (dtype == TQ_F32) {
+        if (g_min > 0.0f) TQ_LAUNCH_PARTIAL(TQ_F32, true); else TQ_LAUNCH_PARTIAL(TQ_F32, false);
+    } else {
+        if (g_min > 0.0f) TQ_LAUNCH_PARTIAL(TQ_BF16, true); else TQ_LAUNCH_PARTIAL(TQ_BF16, false);
+    }
+#undef TQ_LAUNCH_PARTIAL
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     // one workgroup per 64 bins, plus one per bucket for the scalar fields
