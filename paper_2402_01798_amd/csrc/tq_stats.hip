@@ -14,8 +14,8 @@
 //   2. tq_stats_reduce_kernel: a workgroup per (bucket, 64 bins) adds the slices' rows, 16
 //      slices at a time, with coalesced loads; one more workgroup per bucket combines max,
 //      counts and the log-sum.
-// Counts are integers, so the result does not depend on scheduling; the log-sum is added
-// in a fixed order as well.
+// Counts are integers and the tail's log-sum travels as exact integer sums, so the result
+// depends neither on scheduling nor on how the tensor was sliced or batched.
 #include "tq_device.h"
 
 namespace tq {
