@@ -81,27 +81,39 @@ __device__ __forceinline__ double block_exclusive_scan(double local, ParamsLds& 
 
 struct DensityView {
     const ParamsLds& L;
-    double n, absmax;
-    __device__ double covered(int j, double x, double& w) const
+    double n, inv_n, absmax;
+    // Part of bin j below x, as a fraction of the bin (frac) and as a length (len).  The bins
+    // between 2^-40 and 2^16 are 2^(octave-44) wide, so their reciprocal width is exact.
+    __device__ void covered(int j, double x, double& frac, double& len) const
     {
         const double lo = bin_lo(j);
-        w = bin_hi(j, absmax) - lo;
+        double w, rw;
+        if (j >= 1 && j < kNB - 1) {
+            const int e = ((j - 1) >> 4) - 44;
+            w = ldexp(1.0, e);
+            rw = ldexp(1.0, -e);
+        } else {
+            w = bin_hi(j, absmax) - lo;
+            rw = 1.0 / w;
+        }
         double c = x - lo;
-        return c < 0.0 ? 0.0 : (c > w ? w : c);
+        c = c < 0.0 ? 0.0 : (c > w ? w : c);
+        len = c;
+        frac = c * rw;
     }
     __device__ double Q_U(double a) const
     {
         const int j = bin_of(a);
-        double w;
-        const double c = covered(j, a, w);
-        return (L.cum[j] + L.hist[j] * (c / w)) / n;
+        double frac, len;
+        covered(j, a, frac, len);
+        return (L.cum[j] + L.hist[j] * frac) * inv_n;
     }
     __device__ double half_int(double x) const            // int_0^x p^(1/3)
     {
         const int j = bin_of(x);
-        double w;
-        const double c = covered(j, x, w);
-        return L.H[j] + L.p13[j] * c;
+        double frac, len;
+        covered(j, x, frac, len);
+        return L.H[j] + L.p13[j] * len;
     }
     __device__ double Q_N(double a) const
     {
@@ -146,10 +158,12 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_
 #pragma unroll
     for (int k = 0; k < kBinsPerLane; ++k) {
         if (i0 + k < kNB) { L.hist[i0 + k] = h[k]; L.cum[i0 + k] = run; }
+        const double before = run;
         run += h[k];
         // Without a caller-fixed g_min the tail starts at the lower edge of the first bin at
-        // which the cumulative count reaches the 0.9-quantile of |g|.
-        if (i0 + k < kNB && n > 0.0 && 10.0 * run >= 9.0 * n) atomicMin(&L.tail_bin, i0 + k);
+        // which the cumulative count reaches the 0.9-quantile of |g|: exactly one bin has the
+        // count below the mark before it and at or above the mark with it.
+        if (i0 + k < kNB && n > 0.0 && 10.0 * before < 9.0 * n && 10.0 * run >= 9.0 * n) L.tail_bin = i0 + k;
     }
     if (tid == kBlock - 1) L.cum[kNB] = n;
     __syncthreads();
@@ -194,7 +208,7 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_
     const double sum_log_binned = L.total;
     if (tid != 0) return;
 
-    const DensityView D{L, n, absmax};
+    const DensityView D{L, n, n > 0.0 ? 1.0 / n : 0.0, absmax};
     const int s = (1 << bits) - 1;
     uint32_t flags = 0;
     double gamma = 0.0, rho = 0.0, alpha;
