@@ -38,13 +38,17 @@ __device__ __forceinline__ uint32_t load_codes(const uint8_t* p, bool room_for_d
     return w & 0x00FFFFFFu;
 }
 
-__device__ __forceinline__ void store_group(float* o, const float (&acc)[8], uint64_t e0, uint64_t d, int accumulate)
+// ACC is a template parameter on purpose: with a run-time flag the read-modify-write branch
+// leaves "a load may be pending" on every path, and the compiler then waits for ALL
+// outstanding memory operations -- the tile's own stores included -- before the next tile.
+template <bool ACC>
+__device__ __forceinline__ void store_group(float* o, const float (&acc)[8], uint64_t e0, uint64_t d)
 {
     if (e0 + kGroup <= d) {
         float4* o4 = reinterpret_cast<float4*>(o);
         float4 a = make_float4(acc[0], acc[1], acc[2], acc[3]);
         float4 b = make_float4(acc[4], acc[5], acc[6], acc[7]);
-        if (accumulate) {
+        if constexpr (ACC) {
             const float4 pa = o4[0], pb = o4[1];
             a.x = pa.x + a.x; a.y = pa.y + a.y; a.z = pa.z + a.z; a.w = pa.w + a.w;
             b.x = pb.x + b.x; b.y = pb.y + b.y; b.z = pb.z + b.z; b.w = pb.w + b.w;
@@ -52,10 +56,17 @@ __device__ __forceinline__ void store_group(float* o, const float (&acc)[8], uin
         o4[0] = a;
         o4[1] = b;
     } else {                                  // ragged end of the tensor
+        // A rolled loop on purpose: unrolled, its last store was merged into the vector path
+        // above, which then wrote 16 + 12 + 4 bytes per lane and lost a third of the bandwidth.
         const int n_valid = (int)(d - e0);
+#pragma clang loop unroll(disable)
+        for (int j = 0; j < n_valid; ++j) {
+            float v = acc[0];
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (j < n_valid) o[j] = accumulate ? o[j] + acc[j] : acc[j];
+            for (int k = 1; k < 8; ++k) v = (j == k) ? acc[k] : v;
+            if constexpr (ACC) v = o[j] + v;
+            o[j] = v;
+        }
     }
 }
 
@@ -72,9 +83,9 @@ __device__ __forceinline__ void fill_level_rows(float* table, const DecodeArgs& 
     }
 }
 
-// tq_decode_fast_kernel<BITS, U, T>: U = workers handled (N rounded up to 1, 2, 4, 8 or 16;
+// tq_decode_fast_kernel<BITS, U, T, ACC>: U = workers handled (N rounded up to 1, 2, 4, 8 or 16;
 // the rows of the missing workers are zero and their stream is worker 0's, so they add 0),
-// T = tiles per workgroup.
+// T = tiles per workgroup, ACC = add to `out` instead of overwriting it.
 //
 // One shot per workgroup, no loop over tiles: on this ISA loads and stores retire through ONE
 // in-order counter, so a wave that stores a tile and then waits for further loads also waits
@@ -83,10 +94,10 @@ __device__ __forceinline__ void fill_level_rows(float* table, const DecodeArgs& 
 // exactly one: the code words of all T tiles are requested first; meanwhile each wavefront
 // fetches the level rows of "its" workers through a scalar (wave-uniform) pointer, expands
 // them to pair entries with two cross-lane reads and writes them to LDS; one barrier.
-template <int BITS, int U, int T>
+template <int BITS, int U, int T, bool ACC>
 __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     const DecodeArgs args, int N, int weighted, float scale, uint64_t d, uint64_t d_pad, uint64_t bucket_elems,
-    uint32_t groups_per_bucket, int accumulate, uint64_t payload_bytes, float* __restrict__ out)
+    uint32_t groups_per_bucket, uint64_t payload_bytes, float* __restrict__ out)
 {
     constexpr int PAIRS = 1 << (2 * BITS);
     constexpr uint32_t PMASK = PAIRS - 1;
@@ -148,9 +159,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     __syncthreads();
     const float post = weighted ? 1.0f : scale;                // x * 1.0f is exact
 
-#pragma unroll
-    for (int t = 0; t < T; ++t) {
-        float acc[8];
+    auto lookup = [&](int t, float (&acc)[8]) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
 #pragma unroll
@@ -163,7 +172,24 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
             }
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = acc[j] * post;
-        if (e0[t] < bend) store_group(out + e0[t], acc, e0[t], d, accumulate);
+    };
+
+    if (gstart + (uint64_t)T * kTile <= bend) {
+        // Every lane of the workgroup owns a whole group (all but the last workgroup of a
+        // bucket): straight-line code, each tile stored as soon as it is looked up.
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            float acc[8];
+            lookup(t, acc);
+            store_group<ACC>(out + e0[t], acc, 0, kGroup);
+        }
+    } else {
+        float acc[T][8];
+#pragma unroll
+        for (int t = 0; t < T; ++t) lookup(t, acc[t]);
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+            if (e0[t] < bend) store_group<ACC>(out + e0[t], acc[t], e0[t], d);
     }
 }
 
@@ -199,7 +225,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = acc[j] * scale;
     }
-    store_group(out + e0, acc, e0, d, accumulate);
+    if (accumulate) store_group<true>(out + e0, acc, e0, d); else store_group<false>(out + e0, acc, e0, d);
 }
 
 }  // namespace tq
@@ -232,8 +258,14 @@ hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const
         const dim3 blocks((unsigned)nblocks);
         const int U = N <= 1 ? 1 : (N <= 2 ? 2 : (N <= 4 ? 4 : (N <= 8 ? 8 : 16)));
 #define TQ_LAUNCH_FAST(B, UU)                                                                               \
-    hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, T>), blocks, threads, 0, st, args, N, weighted, scale, \
-                       d, d_pad, be, (uint32_t)gpb, accumulate, pbytes, out)
+    do {                                                                                                    \
+        if (accumulate)                                                                                     \
+            hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, T, true>), blocks, threads, 0, st, args, N, \
+                               weighted, scale, d, d_pad, be, (uint32_t)gpb, pbytes, out);                  \
+        else                                                                                                \
+            hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, T, false>), blocks, threads, 0, st, args, N, \
+                               weighted, scale, d, d_pad, be, (uint32_t)gpb, pbytes, out);                  \
+    } while (0)
 #define TQ_LAUNCH_FAST_U(B)                     \
     switch (U) {                                \
         case 1: TQ_LAUNCH_FAST(B, 1); break;    \
