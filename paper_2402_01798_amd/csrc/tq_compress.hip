@@ -40,6 +40,20 @@ struct LevelLds {
     float2 e[16];
 };
 
+// NaN -> +0 for a lane's 8 values.  NaN is rare, so the test is made as cheap as it can be:
+// one unordered compare per PAIR of values, and the replacement itself only in wavefronts
+// in which some lane saw one.
+__device__ __forceinline__ void replace_nan(float (&x)[8])
+{
+    unsigned long long any = 0ull;                             // lane masks, combined on the scalar unit
+#pragma unroll
+    for (int i = 0; i < 4; ++i) any |= __builtin_amdgcn_ballot_w64(__builtin_isunordered(x[2 * i], x[2 * i + 1]));
+    if (any != 0ull) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = (x[j] != x[j]) ? 0.0f : x[j];
+    }
+}
+
 // Eq. (1) then Eq. (2) for one element; `rf` is the element's 16-bit draw as a float.
 // The dither is rnd = (rf + 1/2) / 2^16 and the code is k + [frac + rnd >= 1].
 template <int BITS, int GRID>
@@ -47,8 +61,7 @@ __device__ __forceinline__ uint32_t quantize(float x, float rf, float alpha, flo
                                              const float (&lv)[16], const LevelLds& tab)
 {
     constexpr uint32_t S = (1u << BITS) - 1u;
-    x = (x != x) ? 0.0f : x;                                   // NaN -> +0
-    const float xc = __builtin_amdgcn_fmed3f(x, -alpha, alpha);  // Eq. (1); x is not NaN here
+    const float xc = __builtin_amdgcn_fmed3f(x, -alpha, alpha);  // Eq. (1); the caller has replaced NaN
     if constexpr (GRID == TQ_GRID_UNIFORM) {
         // position in units of cells from -alpha, plus the dither's half grain; then the draw
         const float u = fmaf(xc, inv_step, 0.5f * (float)S + 1.0f / 131072.0f);
@@ -131,6 +144,8 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
         load_group<DTYPE>(g, e0, x);                            // in flight while the draw is computed
         uint32_t rw[4];
         draw(rw);
+        asm volatile("" : "+v"(rw[0]));                        // the draw is computed here, under the loads
+        replace_nan(x);
         word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab)
                           : encode_group<BITS, TQ_GRID_UNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab);
     } else if (e0 < d) {                                       // ragged end of the tensor
@@ -140,6 +155,7 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
         for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, e0 + j) : 0.0f;
         uint32_t rw[4];
         draw(rw);
+        replace_nan(x);
         word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab)
                           : encode_group<BITS, TQ_GRID_UNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab);
     }

@@ -12,10 +12,19 @@ constexpr int kGroup = 8;            // elements served by one Philox4x32 call =
 constexpr int kBlock = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int kTile = kBlock * kGroup;  // elements per workgroup tile (2048)
 
+// a ^ b ^ c in one instruction (the three-input bitwise operation of this ISA, truth table 0x96).
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 // Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies whose
 // halves are crossed over and xored with a Weyl-sequence round key.  Operands that are
 // uniform over the wavefront (key, worker, step, high counter word) stay in SGPRs and
-// their multiplies run on the scalar unit; only the lane's counter word is per-lane.
+// their multiplies run on the scalar unit; only the lane's counter word c0 is per-lane.
+// The xors of the first three rounds are grouped so that the uniform pair is combined on
+// the scalar unit (round 1: c1, c2, c3 uniform; round 2: c0, c1; round 3: c3); from then
+// on every word differs per lane and each output word is one three-input xor.
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t (&out)[4])
 {
@@ -23,8 +32,12 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     for (int r = 0; r < 10; ++r) {
         const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
         const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t h0 = (uint32_t)(p0 >> 32), h1 = (uint32_t)(p1 >> 32);
+        uint32_t n0, n2;
+        if (r == 0) { n0 = h1 ^ c1 ^ k0; n2 = h0 ^ (c3 ^ k1); }
+        else if (r == 1) { n0 = h1 ^ (c1 ^ k0); n2 = c3 ^ (h0 ^ k1); }
+        else if (r == 2) { n0 = xor3(h1, c1, k0); n2 = h0 ^ (c3 ^ k1); }
+        else { n0 = xor3(h1, c1, k0); n2 = xor3(h0, c3, k1); }
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
