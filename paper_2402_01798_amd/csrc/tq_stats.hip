@@ -32,14 +32,15 @@ constexpr int kReduceBins = 64;
 constexpr int kBinBias = 1391;                         // 16 * (biased exponent of 2^-40) - 1
 
 // Per (bucket, slice).  The log-sum of the tail travels as two exact integer sums (ln(a/g_min)
-// = ln2 (exponent + log2 mantissa) - ln g_min, the log2 of the mantissa in 2^-32 fixed point),
-// so the final value does not depend on how the tensor was cut into slices or batched.
+// = ln2 (exponent + log2 mantissa) - ln g_min; the log2 of the mantissas is taken once per
+// aligned group of 8 elements, of their product, and kept in 2^-28 fixed point), so the final
+// value does not depend on how the tensor was cut into slices or batched.
 struct StatsExtra {            // 32 bytes
     uint32_t absmax_bits;
     uint32_t n_nonfinite;
     unsigned long long n_tail;
     long long exp_sum;             // sum of unbiased exponents of the tail elements
-    unsigned long long log2m_fix;  // sum of log2(mantissa in [1,2)) * 2^32 of the tail elements
+    unsigned long long log2m_fix;  // sum over groups of log2(product of the tail mantissas) * 2^28
 };
 
 __host__ __device__ inline uint64_t stats_ws_hist_words(uint64_t nb, uint32_t slices)
@@ -108,29 +109,55 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     uint32_t* my_hist = hist + (threadIdx.x & (kStatsReplicas - 1)) * kStatsStride;
     const uint32_t gmin_bits = __float_as_uint(g_min);
     uint32_t amax_bits = 0u, nonfinite = 0u, n_tail = 0u;
-    int32_t exp_sum = 0;                 // sum of unbiased exponents of the tail elements
-    unsigned long long log2m_fix = 0ull; // sum of log2(mantissa in [1,2)) in 2^-32 fixed point
+    uint32_t not_counted = 0u;           // values this lane put into bin 0 that do not belong there
+    uint32_t exp_acc = 0u;               // sum of BIASED exponents of the tail elements
+    unsigned long long log2m_fix = 0ull; // sum of log2(product of 8 mantissas in [1,2)) in 2^-28 fixed point
 
-    // One magnitude into the lane's running statistics.  Branch-free: NaN and Inf are counted
-    // into a spare slot behind the last bin of the lane's replica, so the loop body below is
-    // straight-line code and the next trip's loads can stay in flight across it.
-    auto take = [&](uint32_t raw) {
-        const uint32_t a = raw & 0x7FFFFFFFu;                          // |g| as an ordered integer
-        const bool finite = a < 0x7F800000u;
-        int32_t idx = (int32_t)(a >> 19) - kBinBias;
-        idx = idx < 0 ? 0 : (idx > TQ_NBINS - 1 ? TQ_NBINS - 1 : idx);
-        idx = finite ? idx : TQ_NBINS;                                 // spare slot, never flushed
-        atomicAdd(&my_hist[idx], 1u);
-        nonfinite += finite ? 0u : 1u;
-        const uint32_t af = finite ? a : 0u;
-        amax_bits = af > amax_bits ? af : amax_bits;
+    // Eight magnitudes (one lane's group of consecutive elements) into the lane's running
+    // statistics.  NaN and Inf are rare, so the common path does not test for them per value:
+    // the largest of the eight tells whether the wavefront saw one at all, and only then are
+    // they counted and replaced by 0 -- which lands in bin 0 and is taken out of it again
+    // before the counts are written.  The tail's log-sum costs one logarithm per group: the
+    // eight mantissas (1.0 for a value outside the tail) are multiplied in a fixed tree order.
+    auto take_group = [&](const uint32_t (&raw)[8]) {
+        uint32_t a[8];                                                 // |g| as ordered integers
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a[j] = raw[j] & 0x7FFFFFFFu;
+        auto max8 = [&]() {
+            const uint32_t m01 = a[0] > a[1] ? a[0] : a[1], m23 = a[2] > a[3] ? a[2] : a[3];
+            const uint32_t m45 = a[4] > a[5] ? a[4] : a[5], m67 = a[6] > a[7] ? a[6] : a[7];
+            const uint32_t m03 = m01 > m23 ? m01 : m23, m47 = m45 > m67 ? m45 : m67;
+            return m03 > m47 ? m03 : m47;
+        };
+        uint32_t m = max8();
+        if (__builtin_amdgcn_ballot_w64(m >= 0x7F800000u) != 0ull) {   // wavefront-uniform, rare
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool finite = a[j] < 0x7F800000u;
+                nonfinite += finite ? 0u : 1u;
+                a[j] = finite ? a[j] : 0u;
+            }
+            m = max8();
+        }
+        amax_bits = m > amax_bits ? m : amax_bits;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            int32_t idx = (int32_t)(a[j] >> 19) - kBinBias;
+            idx = idx < 0 ? 0 : (idx > TQ_NBINS - 1 ? TQ_NBINS - 1 : idx);
+            atomicAdd(&my_hist[idx], 1u);
+        }
         if constexpr (TAIL) {                                          // g_min >= 2^-40: a tail value is normal
-            const bool in_tail = finite && a > gmin_bits;
-            n_tail += in_tail ? 1u : 0u;
-            exp_sum += in_tail ? (int32_t)(a >> 23) - 127 : 0;
-            const float l2 = __log2f(__uint_as_float((a & 0x007FFFFFu) | 0x3F800000u));   // in [0, 1]
-            const uint32_t fix = (uint32_t)(l2 * 4294967296.0f);       // saturating conversion
-            log2m_fix += in_tail ? fix : 0u;
+            float mant[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool in_tail = a[j] > gmin_bits;
+                n_tail += in_tail ? 1u : 0u;
+                const uint32_t am = in_tail ? a[j] : 0u;              // exponent 0, mantissa 1.0 outside the tail
+                exp_acc += am >> 23;
+                mant[j] = __uint_as_float((am & 0x007FFFFFu) | 0x3F800000u);
+            }
+            const float prod = ((mant[0] * mant[1]) * (mant[2] * mant[3])) * ((mant[4] * mant[5]) * (mant[6] * mant[7]));
+            log2m_fix += (uint32_t)(__log2f(prod) * 268435456.0f);     // prod in [1, 256]: at most 2^31
         }
     };
 
@@ -152,9 +179,7 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
         };
         auto consume = [&](const uint32_t (&buf)[kTrip][8]) {
 #pragma unroll
-            for (int t = 0; t < kTrip; ++t)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) take(buf[t][j]);
+            for (int t = 0; t < kTrip; ++t) take_group(buf[t]);
         };
         request(bufA, 0);
         const uint32_t pairs = n_trips >> 1;
@@ -174,15 +199,25 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
         if (e0 + kGroup <= cend) {
             uint32_t b0[8];
             load_bits<DTYPE>(g, e0, b0);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) take(b0[j]);
+            take_group(b0);
         } else {                                                       // ragged end of the tensor
-            for (uint64_t e = e0; e < cend; ++e) {
-                if constexpr (DTYPE == TQ_F32) take(static_cast<const uint32_t*>(g)[e]);
-                else take((uint32_t) static_cast<const uint16_t*>(g)[e] << 16);
+            const int n_valid = (int)(cend - e0);                      // the absent values enter as 0
+            uint32_t b0[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                b0[j] = 0u;
+                if (j < n_valid) {
+                    if constexpr (DTYPE == TQ_F32) b0[j] = static_cast<const uint32_t*>(g)[e0 + j];
+                    else b0[j] = (uint32_t) static_cast<const uint16_t*>(g)[e0 + j] << 16;
+                }
             }
+            take_group(b0);
+            not_counted += (uint32_t)(8 - n_valid);
         }
     }
+    // NaN, Inf and the absent values of a ragged group were counted as zeros: take them out again
+    not_counted += nonfinite;
+    if (not_counted) atomicSub(&my_hist[0], not_counted);
     __syncthreads();
 
     // partial counts of this slice, every bin (the workspace is not pre-cleared), one
@@ -200,9 +235,9 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     amax_bits = wave_reduce_max(amax_bits);
     nonfinite = wave_reduce_add(nonfinite);
     const unsigned long long nt = wave_reduce_add((unsigned long long)n_tail);
-    const long long es = wave_reduce_add((long long)exp_sum);
+    const unsigned long long es = wave_reduce_add((unsigned long long)exp_acc);
     const unsigned long long lf = wave_reduce_add(log2m_fix);
-    if (lane == 0) { red_u32[0][wave] = amax_bits; red_u32[1][wave] = nonfinite; red_u64[0][wave] = nt; red_u64[1][wave] = (unsigned long long)es; red_u64[2][wave] = lf; }
+    if (lane == 0) { red_u32[0][wave] = amax_bits; red_u32[1][wave] = nonfinite; red_u64[0][wave] = nt; red_u64[1][wave] = es; red_u64[2][wave] = lf; }
     __syncthreads();
     if (threadIdx.x == 0) {
         StatsExtra x{0u, 0u, 0ull, 0ll, 0ull};
@@ -213,6 +248,7 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
             x.exp_sum += (long long)red_u64[1][w];
             x.log2m_fix += red_u64[2][w];
         }
+        x.exp_sum -= 127ll * (long long)x.n_tail;                      // biased -> unbiased exponents
         ws_extra[(uint64_t)bucket * slices + slice] = x;
     }
 }
@@ -269,7 +305,7 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
         // ln(a / g_min) = ln2 * (exponent + log2 mantissa) - ln g_min, from exact integer sums
         double sum_log = 0.0;
         if (n_tail)
-            sum_log = 0.6931471805599453 * ((double)exp_sum + (double)log2m_fix * 2.3283064365386963e-10) -
+            sum_log = 0.6931471805599453 * ((double)exp_sum + (double)log2m_fix * 3.725290298461914e-09) -
                       (double)n_tail * log((double)g_min);
         if (lane == 0) {
             const uint64_t lo = (uint64_t)bucket * bucket_elems;
@@ -294,21 +330,39 @@ struct StatsPlan {
     uint32_t slices;
 };
 
-// Slices per bucket.  Measured on MI355X: the partial kernel is fastest with about one
-// 512-thread workgroup per compute unit in the whole launch (each workgroup pays for clearing
-// and flushing its LDS histograms, so fewer, longer-lived workgroups win as long as every CU
-// has one), i.e. about 256 workgroups over all tensors and buckets of the batch.
+// Most slices a bucket is ever cut into: slices of at least 16384 elements, and no more than
+// about one workgroup per compute unit when a single tensor is processed.  The workspace is
+// sized for this many.
+uint32_t max_slices(uint64_t be, uint64_t nb)
+{
+    const uint64_t want = (be + tq::kStatsMinSlice - 1) / tq::kStatsMinSlice;
+    uint64_t cap = (tq::kStatsTargetGroups + nb - 1) / nb;
+    cap = cap > tq::kStatsMaxSlices ? tq::kStatsMaxSlices : cap;
+    const uint64_t m = want < cap ? want : cap;
+    return (uint32_t)(m < 1 ? 1 : m);
+}
+
+// Slices per bucket for a batch of `count` tensors.  Measured on MI355X: the partial kernel is
+// fastest with about one 512-thread workgroup per compute unit in the whole launch (each
+// workgroup pays for clearing and flushing its LDS histograms -- about what reading 16384
+// elements costs -- so fewer, longer-lived workgroups win as long as every CU has one), and a
+// launch of W workgroups takes ceil(W / 256) times one workgroup's time: 357 workgroups are as
+// slow as 512.  The slice count minimises that product.
 StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems, int count)
 {
     StatsPlan p;
     p.be = bucket_elems ? bucket_elems : d;
     p.nb = (d + p.be - 1) / p.be;
-    uint64_t want = (p.be + tq::kStatsMinSlice - 1) / tq::kStatsMinSlice;   // slices of >= 16384 elements
     const uint64_t units = p.nb * (uint64_t)(count < 1 ? 1 : count);
-    uint64_t cap = (tq::kStatsTargetGroups + units - 1) / units;
-    cap = cap < 1 ? 1 : (cap > tq::kStatsMaxSlices ? tq::kStatsMaxSlices : cap);
-    p.slices = (uint32_t)(want < cap ? want : cap);
-    if (p.slices < 1) p.slices = 1;
+    const uint32_t smax = max_slices(p.be, p.nb);
+    uint32_t best = 1;
+    uint64_t best_cost = ~0ull;
+    for (uint32_t sl = 1; sl <= smax; ++sl) {
+        const uint64_t rounds = (units * sl + tq::kStatsTargetGroups - 1) / tq::kStatsTargetGroups;
+        const uint64_t cost = rounds * ((p.be + sl - 1) / sl + (uint64_t)tq::kStatsMinSlice);
+        if (cost < best_cost) { best_cost = cost; best = sl; }
+    }
+    p.slices = best;
     const uint64_t per = (p.be + p.slices - 1) / p.slices;
     p.slice_elems = (per + tq::kStatsTile - 1) / tq::kStatsTile * tq::kStatsTile;
     return p;
@@ -319,9 +373,11 @@ StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems, int count)
 uint64_t tq_stats_workspace_bytes_impl(uint64_t d, uint64_t bucket_elems)
 {
     if (d == 0) return 0;
-    const StatsPlan p = plan_stats(d, bucket_elems, 1);                // a batch never uses more slices
-    const uint64_t hist_bytes = tq::stats_ws_hist_words(p.nb, p.slices) * 4;
-    const uint64_t bytes = (hist_bytes + 15) / 16 * 16 + p.nb * p.slices * sizeof(tq::StatsExtra);
+    const uint64_t be = bucket_elems ? bucket_elems : d;
+    const uint64_t nb = (d + be - 1) / be;
+    const uint32_t slices = max_slices(be, nb);                        // no plan uses more
+    const uint64_t hist_bytes = tq::stats_ws_hist_words(nb, slices) * 4;
+    const uint64_t bytes = (hist_bytes + 15) / 16 * 16 + nb * slices * sizeof(tq::StatsExtra);
     return (bytes + 255) / 256 * 256;                                  // regions of a batch stay aligned
 }
 
