@@ -1,0 +1,76 @@
+"""The paper's central claims on synthetic heavy-tailed data, measured on the GPU library
+through the C ABI (stats -> params -> compress -> decode of one worker): the squared error of
+the round trip is what Lemma 1 plus Eq. (1) predict for the codebook the library designed,
+Sec. IV-A's model bounds it, truncation at the formula's alpha beats no truncation (the
+QSGD / NQSGD baselines, alpha = max|g|), the formula's alpha is close to the best of a sweep,
+and the non-uniform codebook of Sec. IV-B beats the uniform one at equal bits."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import binding as O
+from paper_2402_01798_amd import binding as B
+from error_model_common import SWEEP, X_MIN, expected_mse, model_uniform, pareto_sample
+
+pytestmark = pytest.mark.gpu
+D = (1 << 21) + 4321
+
+
+class Device:
+    def __init__(self):
+        self.g_np = pareto_sample(D, 12)
+        self.g = torch.from_numpy(self.g_np).cuda()
+        self.stats = B.alloc_stats(D)
+        self.params = B.alloc_params(D)
+        self.out = torch.empty(D, dtype=torch.float32, device="cuda")
+        B.tq_stats(self.g, self.stats, B.alloc_stats_workspace(D), 0, X_MIN)
+
+    def design(self, bits, grid, alpha_override=0.0):
+        B.tq_params(self.stats, self.params, bits, grid, alpha_override)
+        torch.cuda.synchronize()
+        return B.params_to_numpy(self.params).view(O.PARAMS_DTYPE).copy()
+
+    def roundtrip_mse(self, bits, grid, alpha_override=0.0):
+        """(record the library designed, squared error of its own compress -> decode)."""
+        P = self.design(bits, grid, alpha_override)
+        pay = B.alloc_payload(D, bits)
+        B.tq_compress(self.g, self.params, pay, bits, 99, 0, 3)
+        B.tq_decompress_aggregate([pay], [self.params], self.out, bits)
+        torch.cuda.synchronize()
+        err = self.out.cpu().numpy().astype(np.float64) - self.g_np.astype(np.float64)
+        return P, float(np.mean(err * err))
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return Device()
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("grid", [0, 1])
+def test_round_trip_error_is_the_expected_one(dev, bits, grid):
+    P, mse = dev.roundtrip_mse(bits, grid)
+    assert abs(mse / expected_mse(dev.g_np, P) - 1.0) < 0.01
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_model_of_sec_4a_bounds_the_uniform_error(dev, bits):
+    P, mse = dev.roundtrip_mse(bits, 0)
+    m = model_uniform(dev.g_np, P)
+    assert 0.5 * m < mse < 1.05 * m
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("grid", [0, 1])
+def test_truncation_helps_and_formula_alpha_is_near_the_best(dev, bits, grid):
+    P, mse = dev.roundtrip_mse(bits, grid)
+    _, no_trunc = dev.roundtrip_mse(bits, grid, -1.0)                  # alpha = max|g|
+    assert mse < no_trunc / (20.0 if grid == 0 else 1.0)
+    a = float(P["alpha"][0])
+    sweep = [dev.roundtrip_mse(bits, grid, a * f)[1] for f in SWEEP]
+    assert mse <= 1.2 * min(sweep)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_nonuniform_codebook_beats_uniform(dev, bits):
+    assert dev.roundtrip_mse(bits, 1)[1] < dev.roundtrip_mse(bits, 0)[1]
