@@ -67,6 +67,10 @@ def lib():
         L.tqo_decompress_aggregate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p,
                                                C.c_int, C.c_uint64, C.c_uint64,
                                                C.c_int, C.c_int, C.c_void_p]
+        L.tqo_decompress_aggregate_update.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p,
+                                                      C.c_int, C.c_uint64, C.c_uint64, C.c_int,
+                                                      C.c_float, C.c_float, C.c_float,
+                                                      C.c_void_p, C.c_void_p]
         L.tqo_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                      C.c_int, C.c_void_p]
         L.tqo_sizeof_stats.restype = C.c_size_t
@@ -164,6 +168,25 @@ def decompress_aggregate(payloads, params, d, bits, bucket_elems=0, weights=None
                                           N, d, bucket_elems, bits, int(accumulate),
                                           _ptr(out)), "tqo_decompress_aggregate")
     return out
+
+
+def decompress_aggregate_update(payloads, params, theta, bits, eta, momentum=0.0,
+                                weight_decay=0.0, velocity=None, bucket_elems=0, weights=None):
+    """Alg. 1's two server steps in place on ``theta`` (and ``velocity`` when given), float32."""
+    N = len(payloads)
+    assert theta.dtype == np.float32 and theta.flags.c_contiguous
+    assert velocity is None or (velocity.dtype == np.float32 and velocity.flags.c_contiguous
+                                and velocity.size == theta.size)
+    payloads = [np.ascontiguousarray(p, dtype=np.uint8) for p in payloads]
+    params = [np.ascontiguousarray(p, dtype=PARAMS_DTYPE).reshape(-1) for p in params]
+    pp = (C.c_void_p * N)(*[p.ctypes.data for p in payloads])
+    qq = (C.c_void_p * N)(*[p.ctypes.data for p in params])
+    w = None if weights is None else np.ascontiguousarray(weights, dtype=np.float32)
+    _check(lib().tqo_decompress_aggregate_update(
+        pp, qq, None if w is None else _ptr(w), N, theta.size, bucket_elems, bits, eta, momentum,
+        weight_decay, _ptr(theta), None if velocity is None else _ptr(velocity)),
+        "tqo_decompress_aggregate_update")
+    return theta
 
 
 def dequantize(payload, params, d, bits, bucket_elems=0):

@@ -13,6 +13,7 @@
  *                           codebook L = {l_0..l_s}, s = 2^b - 1
  *   tqo_compress            Alg. 1, client step "quantize, send"
  *   tqo_decompress_aggregate Alg. 1, server step  g_bar = sum_i w_i g_hat_i
+ *   tqo_decompress_aggregate_update  ... followed by theta <- theta - eta g_bar
  *   tqo_stats               Sec. V (MLE of the tail index), Sec. IV (rho,
  *                           Q_U, integral of p^(1/3)): the raw reductions
  * The parameter design of Sec. IV (alpha fixed points, level tables) lives in
@@ -273,6 +274,26 @@ static uint32_t read_code(const uint8_t *payload, uint64_t e, uint32_t bits)
  * order 0..N-1 in binary32 and the sum is multiplied once by (float)(1/N).
  * With weights, each term is w_i * L_i[c] (one rounding) and the terms are
  * added in worker order.  accumulate != 0 adds the result to out[e]. */
+static int aggregate_one(const uint8_t *const *payload,
+                         const tqo_params_t *const *params, const float *weights,
+                         int N, uint64_t e, uint64_t bucket_elems, int bits,
+                         float *g_bar)
+{
+    const uint64_t b = bucket_of(e, bucket_elems);
+    const float w_uniform = 1.0f / (float)N;
+    float acc = 0.0f;
+    for (int i = 0; i < N; ++i) {
+        const tqo_params_t *P = &params[i][b];
+        if ((int)P->bits != bits) return TQO_EINVAL;
+        float term = P->level[read_code(payload[i], e, (uint32_t)bits)];
+        if (weights) term = weights[i] * term;
+        acc = (i == 0) ? term : acc + term;
+    }
+    if (!weights) acc = acc * w_uniform;
+    *g_bar = acc;
+    return TQO_OK;
+}
+
 int tqo_decompress_aggregate(const uint8_t *const *payload,
                              const tqo_params_t *const *params,
                              const float *weights, int N, uint64_t d,
@@ -281,19 +302,49 @@ int tqo_decompress_aggregate(const uint8_t *const *payload,
 {
     if (check_layout(d, bucket_elems) || N < 1 || bits < 2 || bits > 4)
         return TQO_EINVAL;
-    const float w_uniform = 1.0f / (float)N;
     for (uint64_t e = 0; e < d; ++e) {
-        const uint64_t b = bucket_of(e, bucket_elems);
-        float acc = 0.0f;
-        for (int i = 0; i < N; ++i) {
-            const tqo_params_t *P = &params[i][b];
-            if ((int)P->bits != bits) return TQO_EINVAL;
-            float term = P->level[read_code(payload[i], e, (uint32_t)bits)];
-            if (weights) term = weights[i] * term;
-            acc = (i == 0) ? term : acc + term;
-        }
-        if (!weights) acc = acc * w_uniform;
+        float acc;
+        if (aggregate_one(payload, params, weights, N, e, bucket_elems, bits, &acc))
+            return TQO_EINVAL;
         out[e] = accumulate ? out[e] + acc : acc;
+    }
+    return TQO_OK;
+}
+
+/* Alg. 1, the two server steps together: g_bar = sum_i w_i g_hat_i as above,
+ * then theta <- theta - eta * g_bar.  The experiments of Sec. V train with
+ * momentum SGD and weight decay; the paper does not write that recursion out,
+ * so the common form is taken (a reading):
+ *     u     = g_bar + weight_decay * theta     (u = g_bar when weight_decay == 0)
+ *     v     = momentum * v + u                 (only when a velocity is kept)
+ *     theta = theta - eta * v                  (theta - eta * u without velocity)
+ * every product and sum rounded once to binary32, in this order.
+ * velocity == NULL means plain SGD, the update Alg. 1 states. */
+int tqo_decompress_aggregate_update(const uint8_t *const *payload,
+                                    const tqo_params_t *const *params,
+                                    const float *weights, int N, uint64_t d,
+                                    uint64_t bucket_elems, int bits, float eta,
+                                    float momentum, float weight_decay,
+                                    float *theta, float *velocity)
+{
+    if (check_layout(d, bucket_elems) || N < 1 || bits < 2 || bits > 4)
+        return TQO_EINVAL;
+    for (uint64_t e = 0; e < d; ++e) {
+        float g_bar;
+        if (aggregate_one(payload, params, weights, N, e, bucket_elems, bits, &g_bar))
+            return TQO_EINVAL;
+        float u = g_bar;
+        if (weight_decay != 0.0f) {
+            const float decay = weight_decay * theta[e];
+            u = g_bar + decay;
+        }
+        if (velocity) {
+            const float carried = momentum * velocity[e];
+            u = carried + u;
+            velocity[e] = u;
+        }
+        const float step = eta * u;
+        theta[e] = theta[e] - step;
     }
     return TQO_OK;
 }
