@@ -168,6 +168,30 @@ int tq_decompress_aggregate(const void* const* payload_host,
                             uint64_t bucket_elems, int bits, int accumulate,
                             float* out_dev, void* stream);
 
+/*
+ * tq_decompress_aggregate_update -- both server steps of Alg. 1 in one pass: the aggregate
+ * g_bar of tq_decompress_aggregate is not written out but applied to the model,
+ *     theta <- theta - eta * g_bar                       (Alg. 1, last server step),
+ * with the momentum and weight decay of the momentum SGD the experiments of Sec. V train with
+ * (the paper does not write that recursion out; the common form is taken):
+ *     u = g_bar + weight_decay * theta      (u = g_bar when weight_decay == 0)
+ *     v = momentum * v + u                  (only with a velocity buffer)
+ *     theta = theta - eta * v               (theta - eta * u without one)
+ * each product and sum rounded once to binary32, in this order.
+ *   payload_host, params_host, weights_host, N, d, bucket_elems, bits
+ *                 as in tq_decompress_aggregate
+ *   theta_dev     [d] floats, updated in place
+ *   velocity_dev  [d] floats, updated in place, or NULL for plain SGD (momentum is
+ *                 then ignored); must not alias theta_dev
+ * Saves the 4 + 4 bytes per element of writing g_bar and reading it back.
+ */
+int tq_decompress_aggregate_update(const void* const* payload_host,
+                                   const tq_params_t* const* params_host,
+                                   const float* weights_host, int N, uint64_t d,
+                                   uint64_t bucket_elems, int bits, float eta,
+                                   float momentum, float weight_decay, float* theta_dev,
+                                   float* velocity_dev, void* stream);
+
 /* Text for a return code (static storage). */
 const char* tq_strerror(int code);
 

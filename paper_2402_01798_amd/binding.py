@@ -62,13 +62,14 @@ def lib():
         L.tq_params.argtypes = [vp, u64, i32, i32, f32, vp, vp]
         L.tq_compress.argtypes = [vp, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
         L.tq_decompress_aggregate.argtypes = [vp, vp, vp, i32, u64, u64, i32, i32, vp, vp]
+        L.tq_decompress_aggregate_update.argtypes = [vp, vp, vp, i32, u64, u64, i32, f32, f32, f32, vp, vp, vp]
         L.tq_strerror.argtypes = [i32]
         L.tq_strerror.restype = C.c_char_p
         L.tq_stats_multi.argtypes = [vp, i32, i32, u64, u64, f32, vp, vp, u64, vp]
         L.tq_params_multi.argtypes = [vp, i32, u64, i32, i32, f32, vp, vp]
         L.tq_compress_multi.argtypes = [vp, i32, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
         for f in (L.tq_stats, L.tq_params, L.tq_compress, L.tq_decompress_aggregate,
-                  L.tq_stats_multi, L.tq_params_multi, L.tq_compress_multi):
+                  L.tq_decompress_aggregate_update, L.tq_stats_multi, L.tq_params_multi, L.tq_compress_multi):
             f.restype = i32
         _lib = L
     return _lib
@@ -190,14 +191,10 @@ def tq_compress_multi(gs, params, payloads, bits, seed, first_worker, step, buck
     return payloads
 
 
-def tq_decompress_aggregate(payloads, params, out, bits, bucket_elems=0, weights=None,
-                            accumulate=False):
+def _decode_args(payloads, params, d, bits, bucket_elems, weights):
     N = len(payloads)
-    d = out.numel()
     if len(params) != N:
         raise ValueError("one params buffer per payload")
-    if out.dtype != torch.float32:
-        raise TypeError("out must be float32")
     nb = num_buckets(d, bucket_elems)
     for p, q in zip(payloads, params):
         if p.numel() < payload_bytes(d, bits) or q.numel() != nb * PARAMS_BYTES:
@@ -209,9 +206,33 @@ def tq_decompress_aggregate(payloads, params, out, bits, bucket_elems=0, weights
         if len(weights) != N:
             raise ValueError("one weight per worker")
         ww = (C.c_float * N)(*[float(w) for w in weights])
+    return pp, qq, ww, N
+
+
+def tq_decompress_aggregate(payloads, params, out, bits, bucket_elems=0, weights=None,
+                            accumulate=False):
+    d = out.numel()
+    if out.dtype != torch.float32:
+        raise TypeError("out must be float32")
+    pp, qq, ww, N = _decode_args(payloads, params, d, bits, bucket_elems, weights)
     _check(lib().tq_decompress_aggregate(pp, qq, ww, N, d, bucket_elems, bits, int(bool(accumulate)),
                                          _dev(out, "out"), _stream()), "tq_decompress_aggregate")
     return out
+
+
+def tq_decompress_aggregate_update(payloads, params, theta, bits, eta, momentum=0.0, weight_decay=0.0,
+                                   velocity=None, bucket_elems=0, weights=None):
+    d = theta.numel()
+    if theta.dtype != torch.float32 or (velocity is not None and velocity.dtype != torch.float32):
+        raise TypeError("theta and velocity must be float32")
+    if velocity is not None and velocity.numel() != d:
+        raise ValueError("velocity must have theta's size")
+    pp, qq, ww, N = _decode_args(payloads, params, d, bits, bucket_elems, weights)
+    _check(lib().tq_decompress_aggregate_update(
+        pp, qq, ww, N, d, bucket_elems, bits, float(eta), float(momentum), float(weight_decay),
+        _dev(theta, "theta"), None if velocity is None else _dev(velocity, "velocity"), _stream()),
+        "tq_decompress_aggregate_update")
+    return theta
 
 
 def stats_to_numpy(stats):

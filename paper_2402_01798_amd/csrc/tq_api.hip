@@ -14,7 +14,8 @@ hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64
                               uint32_t step, void* const* payload, hipStream_t st);
 hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const* params,
                             const float* weights, int N, uint64_t d, uint64_t bucket_elems, int bits,
-                            int accumulate, float* out, hipStream_t st);
+                            int mode, float eta, float momentum, float weight_decay, float* velocity,
+                            float* out, hipStream_t st);
 
 static_assert(sizeof(tq_stats_t) == 3632, "tq_stats_t layout is part of the interface");
 static_assert(sizeof(tq_params_t) == 160, "tq_params_t layout is part of the interface");
@@ -131,9 +132,10 @@ int tq_compress(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
                              &payload_dev, stream);
 }
 
-int tq_decompress_aggregate(const void* const* payload_host, const tq_params_t* const* params_host,
-                            const float* weights_host, int N, uint64_t d, uint64_t bucket_elems, int bits,
-                            int accumulate, float* out_dev, void* stream)
+// Checks shared by the two server-side calls.
+static int check_decode(const void* const* payload_host, const tq_params_t* const* params_host,
+                        const float* weights_host, int N, uint64_t d, uint64_t bucket_elems, int bits,
+                        const float* out_dev)
 {
     int rc;
     if ((rc = check_layout(d, bucket_elems)) || (rc = check_bits(bits))) return rc;
@@ -145,8 +147,33 @@ int tq_decompress_aggregate(const void* const* payload_host, const tq_params_t* 
         if (!aligned16(payload_host[i]) || !aligned16(params_host[i])) return TQ_EALIGN;
         if (weights_host && weights_host[i] != weights_host[i]) return TQ_EINVAL;
     }
+    return TQ_OK;
+}
+
+int tq_decompress_aggregate(const void* const* payload_host, const tq_params_t* const* params_host,
+                            const float* weights_host, int N, uint64_t d, uint64_t bucket_elems, int bits,
+                            int accumulate, float* out_dev, void* stream)
+{
+    const int rc = check_decode(payload_host, params_host, weights_host, N, d, bucket_elems, bits, out_dev);
+    if (rc) return rc;
     return from_hip(tq_launch_decode(payload_host, params_host, weights_host, N, d, bucket_elems, bits,
-                                     accumulate ? 1 : 0, out_dev, static_cast<hipStream_t>(stream)));
+                                     accumulate ? 1 : 0, 0.0f, 0.0f, 0.0f, nullptr, out_dev,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+int tq_decompress_aggregate_update(const void* const* payload_host, const tq_params_t* const* params_host,
+                                   const float* weights_host, int N, uint64_t d, uint64_t bucket_elems,
+                                   int bits, float eta, float momentum, float weight_decay, float* theta_dev,
+                                   float* velocity_dev, void* stream)
+{
+    const int rc = check_decode(payload_host, params_host, weights_host, N, d, bucket_elems, bits, theta_dev);
+    if (rc) return rc;
+    if (eta != eta || momentum != momentum || weight_decay != weight_decay) return TQ_EINVAL;
+    if (velocity_dev && !aligned16(velocity_dev)) return TQ_EALIGN;
+    if (velocity_dev == theta_dev) return TQ_EINVAL;
+    return from_hip(tq_launch_decode(payload_host, params_host, weights_host, N, d, bucket_elems, bits,
+                                     velocity_dev ? 3 : 2, eta, momentum, weight_decay, velocity_dev, theta_dev,
+                                     static_cast<hipStream_t>(stream)));
 }
 
 const char* tq_strerror(int code)

@@ -38,35 +38,88 @@ __device__ __forceinline__ uint32_t load_codes(const uint8_t* p, bool room_for_d
     return w & 0x00FFFFFFu;
 }
 
-// ACC is a template parameter on purpose: with a run-time flag the read-modify-write branch
-// leaves "a load may be pending" on every path, and the compiler then waits for ALL
-// outstanding memory operations -- the tile's own stores included -- before the next tile.
-template <bool ACC>
-__device__ __forceinline__ void store_group(float* o, const float (&acc)[8], uint64_t e0, uint64_t d)
+// What happens to the aggregate g_bar of an element (the MODE of the kernels below):
+//   kStore        out = g_bar                           Alg. 1, server step "aggregate"
+//   kAccumulate   out = out + g_bar
+//   kSgd          theta = theta - eta * u,  u = g_bar + weight_decay * theta
+//                                                       Alg. 1, server step "update", fused
+//   kSgdMomentum  v = momentum * v + u;  theta = theta - eta * v
+//                                                       the momentum SGD of the Sec. V experiments
+// every product and sum rounded once to binary32, in that order.  MODE is a template parameter
+// on purpose: with a run-time flag the read-modify-write branch leaves "a load may be pending"
+// on every path, and the compiler then waits for ALL outstanding memory operations -- the
+// tile's own stores included -- before the next tile.
+enum { kStore = 0, kAccumulate = 1, kSgd = 2, kSgdMomentum = 3 };
+
+struct Update {
+    float eta, momentum, weight_decay;
+    float* velocity;
+};
+
+template <int MODE>
+__device__ __forceinline__ float finish(float g_bar, float prev, float& vel, const Update& up)
 {
-    if (e0 + kGroup <= d) {
-        float4* o4 = reinterpret_cast<float4*>(o);
-        float4 a = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        float4 b = make_float4(acc[4], acc[5], acc[6], acc[7]);
-        if constexpr (ACC) {
-            const float4 pa = o4[0], pb = o4[1];
-            a.x = pa.x + a.x; a.y = pa.y + a.y; a.z = pa.z + a.z; a.w = pa.w + a.w;
-            b.x = pb.x + b.x; b.y = pb.y + b.y; b.z = pb.z + b.z; b.w = pb.w + b.w;
+    if constexpr (MODE == kStore) {
+        return g_bar;
+    } else if constexpr (MODE == kAccumulate) {
+        return prev + g_bar;
+    } else {
+        float u = g_bar;
+        if (up.weight_decay != 0.0f) {
+            const float decay = up.weight_decay * prev;
+            u = g_bar + decay;
         }
-        o4[0] = a;
-        o4[1] = b;
-    } else {                                  // ragged end of the tensor
-        // A rolled loop on purpose: unrolled, its last store was merged into the vector path
-        // above, which then wrote 16 + 12 + 4 bytes per lane and lost a third of the bandwidth.
-        const int n_valid = (int)(d - e0);
-#pragma clang loop unroll(disable)
-        for (int j = 0; j < n_valid; ++j) {
-            float v = acc[0];
+        if constexpr (MODE == kSgdMomentum) {
+            const float carried = up.momentum * vel;
+            u = carried + u;
+            vel = u;
+        }
+        const float delta = up.eta * u;
+        return prev - delta;
+    }
+}
+
+__device__ __forceinline__ void load8(const float* p, float (&x)[8])
+{
+    const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+__device__ __forceinline__ void store8(float* p, const float (&x)[8])
+{
+    reinterpret_cast<float4*>(p)[0] = make_float4(x[0], x[1], x[2], x[3]);
+    reinterpret_cast<float4*>(p)[1] = make_float4(x[4], x[5], x[6], x[7]);
+}
+
+// A lane's whole group: prev (and vel) were loaded by the caller, early, when MODE needs them.
+template <int MODE>
+__device__ __forceinline__ void finish_group(float* o, uint64_t e0, float (&acc)[8], const float (&prev)[8],
+                                             float (&vel)[8], const Update& up)
+{
 #pragma unroll
-            for (int k = 1; k < 8; ++k) v = (j == k) ? acc[k] : v;
-            if constexpr (ACC) v = o[j] + v;
-            o[j] = v;
-        }
+    for (int j = 0; j < 8; ++j) acc[j] = finish<MODE>(acc[j], prev[j], vel[j], up);
+    store8(o, acc);
+    if constexpr (MODE == kSgdMomentum) store8(up.velocity + e0, vel);
+}
+
+// The ragged end of the tensor, element by element.  A rolled loop on purpose: unrolled, its
+// last store was merged into the vector stores of the whole groups, which then wrote
+// 16 + 12 + 4 bytes per lane and lost a third of the bandwidth.
+template <int MODE>
+__device__ __forceinline__ void finish_ragged(float* o, uint64_t e0, const float (&acc)[8], int n_valid,
+                                              const Update& up)
+{
+#pragma clang loop unroll(disable)
+    for (int j = 0; j < n_valid; ++j) {
+        float v = acc[0];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) v = (j == k) ? acc[k] : v;
+        float prev = 0.0f, vel = 0.0f;
+        if constexpr (MODE != kStore) prev = o[j];
+        if constexpr (MODE == kSgdMomentum) vel = up.velocity[e0 + j];
+        o[j] = finish<MODE>(v, prev, vel, up);
+        if constexpr (MODE == kSgdMomentum) up.velocity[e0 + j] = vel;
     }
 }
 
@@ -83,9 +136,9 @@ __device__ __forceinline__ void fill_level_rows(float* table, const DecodeArgs& 
     }
 }
 
-// tq_decode_fast_kernel<BITS, U, T, ACC>: U = workers handled (N rounded up to 1, 2, 4, 8 or 16;
+// tq_decode_fast_kernel<BITS, U, T, MODE>: U = workers handled (N rounded up to 1, 2, 4, 8 or 16;
 // the rows of the missing workers are zero and their stream is worker 0's, so they add 0),
-// T = tiles per workgroup, ACC = add to `out` instead of overwriting it.
+// T = tiles per workgroup, MODE = what is done with the aggregate (see above).
 //
 // One shot per workgroup, no loop over tiles: on this ISA loads and stores retire through ONE
 // in-order counter, so a wave that stores a tile and then waits for further loads also waits
@@ -94,10 +147,10 @@ __device__ __forceinline__ void fill_level_rows(float* table, const DecodeArgs& 
 // exactly one: the code words of all T tiles are requested first; meanwhile each wavefront
 // fetches the level rows of "its" workers through a scalar (wave-uniform) pointer, expands
 // them to pair entries with two cross-lane reads and writes them to LDS; one barrier.
-template <int BITS, int U, int T, bool ACC>
+template <int BITS, int U, int T, int MODE>
 __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     const DecodeArgs args, int N, int weighted, float scale, uint64_t d, uint64_t d_pad, uint64_t bucket_elems,
-    uint32_t groups_per_bucket, uint64_t payload_bytes, float* __restrict__ out)
+    uint32_t groups_per_bucket, uint64_t payload_bytes, float* __restrict__ out, const Update up)
 {
     constexpr int PAIRS = 1 << (2 * BITS);
     constexpr uint32_t PMASK = PAIRS - 1;
@@ -127,6 +180,18 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
         const uint8_t* stream = args.payload[u < N ? u : 0];
 #pragma unroll
         for (int t = 0; t < T; ++t) w[t][u] = load_codes<BITS>(stream + off[t], room[t]);
+    }
+    // what the epilogue reads back (the old output, the parameters, the velocity) is requested
+    // now as well, for the lanes that own a whole group
+    float prev[T][8], vel[T][8];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { prev[t][j] = 0.0f; vel[t][j] = 0.0f; }
+        if (e0[t] + kGroup <= bend) {
+            if constexpr (MODE != kStore) load8(out + e0[t], prev[t]);
+            if constexpr (MODE == kSgdMomentum) load8(up.velocity + e0[t], vel[t]);
+        }
     }
 
     // pair tables: wavefront `wave` expands workers wave, wave + 4, ...  The wave index is
@@ -181,23 +246,25 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
         for (int t = 0; t < T; ++t) {
             float acc[8];
             lookup(t, acc);
-            store_group<ACC>(out + e0[t], acc, 0, kGroup);
+            finish_group<MODE>(out + e0[t], e0[t], acc, prev[t], vel[t], up);
         }
     } else {
         float acc[T][8];
 #pragma unroll
         for (int t = 0; t < T; ++t) lookup(t, acc[t]);
 #pragma unroll
-        for (int t = 0; t < T; ++t)
-            if (e0[t] < bend) store_group<ACC>(out + e0[t], acc[t], e0[t], d);
+        for (int t = 0; t < T; ++t) {
+            if (e0[t] + kGroup <= bend) finish_group<MODE>(out + e0[t], e0[t], acc[t], prev[t], vel[t], up);
+            else if (e0[t] < bend) finish_ragged<MODE>(out + e0[t], e0[t], acc[t], (int)(bend - e0[t]), up);
+        }
     }
 }
 
-template <int BITS>
+template <int BITS, int MODE>
 __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
     const DecodeArgs args, int N, int weighted, float scale, uint64_t d, uint64_t d_pad,
-    uint64_t bucket_elems, uint32_t tiles_per_bucket, int accumulate, uint64_t payload_bytes,
-    float* __restrict__ out)
+    uint64_t bucket_elems, uint32_t tiles_per_bucket, uint64_t payload_bytes, float* __restrict__ out,
+    const Update up)
 {
     constexpr uint32_t MASK = (1u << BITS) - 1u;
     const TileGeom t = tile_geom(blockIdx.x, d_pad, bucket_elems, tiles_per_bucket);
@@ -212,9 +279,14 @@ __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
     const uint64_t byte_off = (e0 >> 3) * (uint64_t)BITS;
     const bool room = byte_off + 4 <= payload_bytes;
 
-    float acc[8];
+    const bool whole = e0 + kGroup <= d;
+    float acc[8], prev[8], vel[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+    for (int j = 0; j < 8; ++j) { acc[j] = 0.0f; prev[j] = 0.0f; vel[j] = 0.0f; }
+    if (whole) {
+        if constexpr (MODE != kStore) load8(out + e0, prev);
+        if constexpr (MODE == kSgdMomentum) load8(up.velocity + e0, vel);
+    }
     for (int i = 0; i < N; ++i) {
         const uint32_t w = load_codes<BITS>(args.payload[i] + byte_off, room);
         const float* row = table + i * 16;
@@ -225,47 +297,37 @@ __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = acc[j] * scale;
     }
-    if (accumulate) store_group<true>(out + e0, acc, e0, d); else store_group<false>(out + e0, acc, e0, d);
+    if (whole) finish_group<MODE>(out + e0, e0, acc, prev, vel, up);
+    else finish_ragged<MODE>(out + e0, e0, acc, (int)(d - e0), up);
 }
 
 }  // namespace tq
 
-// Host side of tq_decompress_aggregate after the argument checks of the C entry point.
-hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const* params,
-                            const float* weights, int N, uint64_t d, uint64_t bucket_elems, int bits,
-                            int accumulate, float* out, hipStream_t st)
-{
-    tq::DecodeArgs args;
-    for (int i = 0; i < TQ_MAX_WORKERS; ++i) {
-        args.payload[i] = i < N ? static_cast<const uint8_t*>(payload[i]) : nullptr;
-        args.params[i] = i < N ? params[i] : nullptr;
-        args.weight[i] = (i < N && weights) ? weights[i] : 0.0f;
-    }
-    const float scale = 1.0f / (float)N;
-    const uint64_t d_pad = (d + 127) / 128 * 128;
-    const uint64_t be = bucket_elems ? bucket_elems : d_pad;
-    const uint64_t nb = (d_pad + be - 1) / be;
-    const uint64_t tpb = (be + tq::kTile - 1) / tq::kTile;             // tiles per bucket
-    const uint64_t pbytes = tq_payload_bytes(d, bits);
-    const int weighted = weights ? 1 : 0;
-    const dim3 threads(tq::kBlock);
+namespace {
 
-    if (N <= 16 && !(bits == 4 && N > 8)) {
+struct DecodeGeom {
+    tq::DecodeArgs args;
+    int N, weighted, bits;
+    float scale;
+    uint64_t d, d_pad, be, nb, tpb, pbytes;
+};
+
+// One launch with the epilogue MODE fixed at compile time.
+template <int MODE>
+hipError_t launch_mode(const DecodeGeom& g, float* out, const tq::Update& up, hipStream_t st)
+{
+    const dim3 threads(tq::kBlock);
+    const int N = g.N;
+    if (N <= 16 && !(g.bits == 4 && N > 8)) {
         constexpr int T = 2;                                           // tiles per workgroup
-        const uint64_t gpb = (tpb + T - 1) / T;
-        const uint64_t nblocks = nb * gpb;
+        const uint64_t gpb = (g.tpb + T - 1) / T;
+        const uint64_t nblocks = g.nb * gpb;
         if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
         const dim3 blocks((unsigned)nblocks);
         const int U = N <= 1 ? 1 : (N <= 2 ? 2 : (N <= 4 ? 4 : (N <= 8 ? 8 : 16)));
-#define TQ_LAUNCH_FAST(B, UU)                                                                               \
-    do {                                                                                                    \
-        if (accumulate)                                                                                     \
-            hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, T, true>), blocks, threads, 0, st, args, N, \
-                               weighted, scale, d, d_pad, be, (uint32_t)gpb, pbytes, out);                  \
-        else                                                                                                \
-            hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, T, false>), blocks, threads, 0, st, args, N, \
-                               weighted, scale, d, d_pad, be, (uint32_t)gpb, pbytes, out);                  \
-    } while (0)
+#define TQ_LAUNCH_FAST(B, UU)                                                                                \
+    hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, T, MODE>), blocks, threads, 0, st, g.args, N,       \
+                       g.weighted, g.scale, g.d, g.d_pad, g.be, (uint32_t)gpb, g.pbytes, out, up)
 #define TQ_LAUNCH_FAST_U(B)                     \
     switch (U) {                                \
         case 1: TQ_LAUNCH_FAST(B, 1); break;    \
@@ -274,7 +336,7 @@ hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const
         case 8: TQ_LAUNCH_FAST(B, 8); break;    \
         default: TQ_LAUNCH_FAST(B, 16); break;  \
     }
-        switch (bits) {
+        switch (g.bits) {
             case 2: TQ_LAUNCH_FAST_U(2) break;
             case 3: TQ_LAUNCH_FAST_U(3) break;
             default:
@@ -291,22 +353,53 @@ hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const
         return hipGetLastError();
     }
 
-    const uint64_t nblocks = nb * tpb;
+    const uint64_t nblocks = g.nb * g.tpb;
     if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     const dim3 blocks((unsigned)nblocks);
-    switch (bits) {
-        case 2:
-            hipLaunchKernelGGL((tq::tq_decode_kernel<2>), blocks, threads, 0, st, args, N, weighted, scale, d,
-                               d_pad, be, (uint32_t)tpb, accumulate, pbytes, out);
-            break;
-        case 3:
-            hipLaunchKernelGGL((tq::tq_decode_kernel<3>), blocks, threads, 0, st, args, N, weighted, scale, d,
-                               d_pad, be, (uint32_t)tpb, accumulate, pbytes, out);
-            break;
-        default:
-            hipLaunchKernelGGL((tq::tq_decode_kernel<4>), blocks, threads, 0, st, args, N, weighted, scale, d,
-                               d_pad, be, (uint32_t)tpb, accumulate, pbytes, out);
-            break;
+#define TQ_LAUNCH_GENERAL(B)                                                                                 \
+    hipLaunchKernelGGL((tq::tq_decode_kernel<B, MODE>), blocks, threads, 0, st, g.args, N, g.weighted,       \
+                       g.scale, g.d, g.d_pad, g.be, (uint32_t)g.tpb, g.pbytes, out, up)
+    switch (g.bits) {
+        case 2: TQ_LAUNCH_GENERAL(2); break;
+        case 3: TQ_LAUNCH_GENERAL(3); break;
+        default: TQ_LAUNCH_GENERAL(4); break;
     }
+#undef TQ_LAUNCH_GENERAL
     return hipGetLastError();
+}
+
+}  // namespace
+
+// Host side of tq_decompress_aggregate and tq_decompress_aggregate_update after the argument
+// checks of the C entry points.  mode: 0 store, 1 accumulate, 2 SGD step on `out` (= theta),
+// 3 the same with the velocity buffer.
+hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const* params,
+                            const float* weights, int N, uint64_t d, uint64_t bucket_elems, int bits,
+                            int mode, float eta, float momentum, float weight_decay, float* velocity,
+                            float* out, hipStream_t st)
+{
+    DecodeGeom g;
+    for (int i = 0; i < TQ_MAX_WORKERS; ++i) {
+        g.args.payload[i] = i < N ? static_cast<const uint8_t*>(payload[i]) : nullptr;
+        g.args.params[i] = i < N ? params[i] : nullptr;
+        g.args.weight[i] = (i < N && weights) ? weights[i] : 0.0f;
+    }
+    g.N = N;
+    g.bits = bits;
+    g.weighted = weights ? 1 : 0;
+    g.scale = 1.0f / (float)N;
+    g.d = d;
+    g.d_pad = (d + 127) / 128 * 128;
+    g.be = bucket_elems ? bucket_elems : g.d_pad;
+    g.nb = (g.d_pad + g.be - 1) / g.be;
+    g.tpb = (g.be + tq::kTile - 1) / tq::kTile;                        // tiles per bucket
+    g.pbytes = tq_payload_bytes(d, bits);
+    const tq::Update up{eta, momentum, weight_decay, velocity};
+    switch (mode) {
+        case tq::kStore: return launch_mode<tq::kStore>(g, out, up, st);
+        case tq::kAccumulate: return launch_mode<tq::kAccumulate>(g, out, up, st);
+        case tq::kSgd: return launch_mode<tq::kSgd>(g, out, up, st);
+        case tq::kSgdMomentum: return launch_mode<tq::kSgdMomentum>(g, out, up, st);
+        default: return hipErrorInvalidValue;
+    }
 }

@@ -27,7 +27,8 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) == {"tq_num_buckets", "tq_payload_bytes", "tq_stats", "tq_stats_workspace_bytes", "tq_params",
-                          "tq_compress", "tq_decompress_aggregate", "tq_strerror",
+                          "tq_compress", "tq_decompress_aggregate", "tq_decompress_aggregate_update",
+                          "tq_strerror",
                           "tq_stats_multi", "tq_params_multi", "tq_compress_multi"}
     for n in names:
         assert getattr(L, n) is not None
@@ -78,6 +79,13 @@ def test_bad_arguments_are_rejected_without_a_device(L):
     assert L.tq_decompress_aggregate(arr, arr, None, 0, 1000, 0, 3, 0, p, None) == B.EINVAL    # N = 0
     assert L.tq_decompress_aggregate(arr, arr, None, 65, 1000, 0, 3, 0, p, None) == B.EUNSUPPORTED
     assert L.tq_decompress_aggregate(arr, arr, None, 2, 1000, 0, 3, 0, odd, None) == B.EALIGN
+    upd = L.tq_decompress_aggregate_update
+    assert upd(arr, arr, None, 0, 1000, 0, 3, 0.1, 0.9, 0.0, p, None, None) == B.EINVAL      # N = 0
+    assert upd(arr, arr, None, 2, 1000, 0, 5, 0.1, 0.9, 0.0, p, None, None) == B.EINVAL      # bits
+    assert upd(arr, arr, None, 2, 1000, 0, 3, float("nan"), 0.9, 0.0, p, None, None) == B.EINVAL
+    assert upd(arr, arr, None, 2, 1000, 0, 3, 0.1, 0.9, 0.0, None, None, None) == B.EINVAL   # no theta
+    assert upd(arr, arr, None, 2, 1000, 0, 3, 0.1, 0.9, 0.0, p, p, None) == B.EINVAL         # velocity aliases theta
+    assert upd(arr, arr, None, 2, 1000, 0, 3, 0.1, 0.9, 0.0, p, odd, None) == B.EALIGN
     bad = (C.c_void_p * 2)(0x1000, 0)
     assert L.tq_decompress_aggregate(bad, arr, None, 2, 1000, 0, 3, 0, p, None) == B.EINVAL    # null payload
     assert L.tq_strerror(B.EALIGN).decode().startswith("device pointer")
