@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--grid", type=int, default=-1, help="-1 = the workload's first grid")
     ap.add_argument("--launch", default="batched", choices=["batched", "per-worker", "streams"],
                     help="how the N simulated workers are launched (see Path.step)")
+    ap.add_argument("--buffer-sets", type=int, default=2,
+                    help="different input gradients per worker, used in turn (1 = the same buffers every step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="profiling aid: only run device-to-device copies of 1 GiB, the known-size "
@@ -46,14 +48,18 @@ def parse():
 class Path:
     """Device buffers of one workload and the launch sequence of one step."""
 
-    def __init__(self, wl, bits, grid, mode="batched"):
+    def __init__(self, wl, bits, grid, mode="batched", sets=2):
         import torch
         from paper_2402_01798_amd import binding as B
         from paper_2402_01798_amd import synth
         self.B, self.torch = B, torch
         self.wl, self.bits, self.grid = wl, bits, grid
         self.N, self.d, self.be = wl.workers, wl.d, wl.bucket_elems
-        self.g = [synth.make_gradient(wl, i, "cuda") for i in range(self.N)]
+        # `sets` different gradients per worker, used in turn: a step never finds the gradient it
+        # reads left in the memory-side cache by the step before (in training every step's
+        # gradient is new)
+        self.gsets = [[synth.make_gradient(wl, i + 64 * s, "cuda") for i in range(self.N)] for s in range(sets)]
+        self.g = self.gsets[0]
         self.stats = [B.alloc_stats(self.d, self.be) for _ in range(self.N)]
         # one statistics workspace per simulated worker: their chains run on separate streams
         self.ws = [B.alloc_stats_workspace(self.d, self.be) for _ in range(self.N)]
@@ -97,6 +103,7 @@ class Path:
         entry point on one stream.  streams: as per-worker, each worker's stats -> params ->
         compress chain on its own HIP stream, the decode waiting for all of them."""
         torch = self.torch
+        self.g = self.gsets[self.step_no % len(self.gsets)]
         if self.mode == "batched":
             self.stats_all()
             self.params_all()
@@ -125,6 +132,7 @@ class Path:
         """Same launches on one stream, each bracketed by events on the launch stream.
         rec[name] collects (start, end, launches covered)."""
         ev = lambda: self.torch.cuda.Event(enable_timing=True)
+        self.g = self.gsets[self.step_no % len(self.gsets)]
         if self.mode == "batched":
             for name, fn in (("stats", self.stats_all), ("params", self.params_all), ("compress", self.compress_all)):
                 a, b = ev(), ev()
@@ -214,7 +222,7 @@ def main():
     wl = synth.WORKLOADS[a.workload]
     bits = a.bits or wl.bits[0]
     grid = a.grid if a.grid >= 0 else wl.grids[0]
-    path = Path(wl, bits, grid, a.launch)
+    path = Path(wl, bits, grid, a.launch, max(1, a.buffer_sets))
     torch.cuda.synchronize()
 
     if a.kernel_only:
@@ -273,6 +281,7 @@ def main():
         "compress_decode_gbps": round(cd_gbps, 1),
         "compress_decode_hbm_frac": round(cd_bytes / (cd_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
         "launch": a.launch,
+        "buffer_sets": len(path.gsets),
         "stage_us_per_step": {k: round(v, 2) for k, v in avg_us.items()},
         "stage_gbps": {"stats": round(path.N * path.bytes_stats() / avg_us["stats"] / 1e3, 1),
                         "compress": round(comp_gbps, 1),

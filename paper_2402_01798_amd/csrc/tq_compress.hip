@@ -11,13 +11,18 @@ namespace tq {
 template <int DTYPE>
 __device__ __forceinline__ void load_group(const void* g, uint64_t e0, float (&x)[8])
 {
+    // Non-temporal loads: this is the last read of the gradient, so it should not displace
+    // what the memory-side cache still holds of the statistics pass's read of the same
+    // tensors -- the rest of this kernel's input.
     if constexpr (DTYPE == TQ_F32) {
-        const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(g) + e0);
-        const float4 a = p[0], b = p[1];
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const f4* p = reinterpret_cast<const f4*>(static_cast<const float*>(g) + e0);
+        const f4 a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 1);
         x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
         x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
     } else {
-        const uint4 v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(g) + e0);
+        typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+        const u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4*>(static_cast<const uint16_t*>(g) + e0));
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {

@@ -86,10 +86,23 @@ __device__ __forceinline__ void load8(const float* p, float (&x)[8])
     x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
 }
 
+typedef float float4_native __attribute__((ext_vector_type(4)));
+
+// STREAM: the data is not read again soon (the plain aggregate), so it is written with the
+// non-temporal hint and does not stay behind as dirty lines whose write-back would compete
+// with the next kernel's reads; the parameters and the velocity of the fused update are read
+// again by the next step and are stored normally.
+template <bool STREAM>
 __device__ __forceinline__ void store8(float* p, const float (&x)[8])
 {
-    reinterpret_cast<float4*>(p)[0] = make_float4(x[0], x[1], x[2], x[3]);
-    reinterpret_cast<float4*>(p)[1] = make_float4(x[4], x[5], x[6], x[7]);
+    if constexpr (STREAM) {
+        float4_native a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
+        __builtin_nontemporal_store(a, reinterpret_cast<float4_native*>(p));
+        __builtin_nontemporal_store(b, reinterpret_cast<float4_native*>(p) + 1);
+    } else {
+        reinterpret_cast<float4*>(p)[0] = make_float4(x[0], x[1], x[2], x[3]);
+        reinterpret_cast<float4*>(p)[1] = make_float4(x[4], x[5], x[6], x[7]);
+    }
 }
 
 // A lane's whole group: prev (and vel) were loaded by the caller, early, when MODE needs them.
@@ -99,8 +112,8 @@ __device__ __forceinline__ void finish_group(float* o, uint64_t e0, float (&acc)
 {
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = finish<MODE>(acc[j], prev[j], vel[j], up);
-    store8(o, acc);
-    if constexpr (MODE == kSgdMomentum) store8(up.velocity + e0, vel);
+    store8<(MODE == kStore || MODE == kAccumulate)>(o, acc);
+    if constexpr (MODE == kSgdMomentum) store8<false>(up.velocity + e0, vel);
 }
 
 // The ragged end of the tensor, element by element.  A rolled loop on purpose: unrolled, its
