@@ -6,6 +6,10 @@
 // (fp32) or 1 KiB (bf16) of gradient and writes 64*b contiguous bytes.
 #include "tq_device.h"
 
+#ifndef TQ_COMPRESS_TILES
+#define TQ_COMPRESS_TILES 1
+#endif
+
 namespace tq {
 
 template <int DTYPE>
@@ -102,20 +106,46 @@ __device__ __forceinline__ uint32_t encode_group(const float (&x)[8], const uint
     return word;
 }
 
+// `room` = bytes of the payload from `out` on.  A payload is a multiple of 16 bytes, so a
+// group's 2 or 4 bytes are either wholly inside or wholly outside; its 3 bytes at b = 3 can
+// straddle the end (the last, ragged group of a short tensor), hence the per-byte test.
+template <int BITS>
+__device__ __forceinline__ void store_codes(uint8_t* out, uint32_t word, uint64_t room = 4)
+{
+    if constexpr (BITS == 4) {
+        *reinterpret_cast<uint32_t*>(out) = word;
+    } else if constexpr (BITS == 2) {
+        *reinterpret_cast<uint16_t*>(out) = (uint16_t)word;
+    } else {
+        out[0] = (uint8_t)word;
+        if (room > 1) out[1] = (uint8_t)(word >> 8);
+        if (room > 2) out[2] = (uint8_t)(word >> 16);
+    }
+}
+
+// Tiles per workgroup: each lane keeps this many 32-byte (fp32) reads in flight while it
+// computes its draws.
+constexpr int kCompressTiles = TQ_COMPRESS_TILES;
+
 template <int DTYPE, int BITS>
 __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     const PtrTable g_tab, uint64_t d, uint64_t d_pad, uint64_t bucket_elems,
-    uint32_t tiles_per_bucket, const PtrTable params_tab, uint32_t seed_lo,
+    uint32_t groups_per_bucket, const PtrTable params_tab, uint32_t seed_lo,
     uint32_t seed_hi, uint32_t first_worker, uint32_t step, const MutPtrTable payload_tab,
     uint64_t payload_bytes)
 {
-    const TileGeom t = tile_geom(blockIdx.x, d_pad, bucket_elems, tiles_per_bucket);
-    if (t.ebase >= t.eend) return;                             // idle tile of a short last bucket
+    constexpr int T = kCompressTiles;
+    const uint32_t bucket = blockIdx.x / groups_per_bucket;
+    const uint32_t grp = blockIdx.x - bucket * groups_per_bucket;
+    const uint64_t bstart = (uint64_t)bucket * bucket_elems;
+    const uint64_t bend = bstart + bucket_elems < d_pad ? bstart + bucket_elems : d_pad;
+    const uint64_t gbase = bstart + (uint64_t)grp * T * kTile;
+    if (gbase >= bend) return;                                 // idle workgroup of a short last bucket
     // blockIdx.y = tensor of the batch; its worker id keys the random draws
     const void* __restrict__ g = g_tab.p[blockIdx.y];
     uint8_t* __restrict__ payload = static_cast<uint8_t*>(payload_tab.p[blockIdx.y]);
     const uint32_t worker = first_worker + blockIdx.y;
-    const tq_params_t* P = static_cast<const tq_params_t*>(params_tab.p[blockIdx.y]) + t.bucket;
+    const tq_params_t* P = static_cast<const tq_params_t*>(params_tab.p[blockIdx.y]) + bucket;
 
     __shared__ LevelLds tab;
     float lv[16];
@@ -129,51 +159,67 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
         __syncthreads();
     }
 
-    const uint64_t e0 = t.ebase + (uint64_t)threadIdx.x * kGroup;
-    const uint64_t qb = t.ebase >> 3;                          // first group of the tile (uniform)
-    const uint32_t qb_lo = (uint32_t)qb, qb_hi = (uint32_t)(qb >> 32);
-    const uint32_t q_lo = qb_lo + threadIdx.x;
-    const uint64_t byte_off = (qb + threadIdx.x) * (uint64_t)BITS;
-    if (e0 >= t.eend || byte_off >= payload_bytes) return;
-
-    // One Philox call per lane; the high counter word stays scalar unless the low word
-    // wraps inside this tile.
-    auto draw = [&](uint32_t (&rw)[4]) {
+    // One Philox call per lane and tile; the high counter word stays scalar unless the low
+    // word wraps inside the tile.
+    auto draw = [&](uint64_t ebase, uint32_t (&rw)[4]) {
+        const uint64_t qb = ebase >> 3;                        // first group of the tile (uniform)
+        const uint32_t qb_lo = (uint32_t)qb, qb_hi = (uint32_t)(qb >> 32);
+        const uint32_t q_lo = qb_lo + threadIdx.x;
         if (qb_lo <= 0xFFFFFFFFu - kBlock) philox4x32_10(q_lo, qb_hi, worker, step, seed_lo, seed_hi, rw);
         else philox4x32_10(q_lo, qb_hi + (q_lo < qb_lo ? 1u : 0u), worker, step, seed_lo, seed_hi, rw);
     };
 
-    uint32_t word = 0;
-    if (e0 + kGroup <= d) {
-        float x[8];
-        load_group<DTYPE>(g, e0, x);                            // in flight while the draw is computed
-        uint32_t rw[4];
-        draw(rw);
-        asm volatile("" : "+v"(rw[0]));                        // the draw is computed here, under the loads
-        replace_nan(x);
-        word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab)
-                          : encode_group<BITS, TQ_GRID_UNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab);
-    } else if (e0 < d) {                                       // ragged end of the tensor
-        const int n_valid = (int)(d - e0);
-        float x[8];
+    const uint64_t lim = bend < d ? bend : d;
+    if (gbase + (uint64_t)T * kTile <= lim) {
+        // every lane owns a whole group in every tile: all reads first, the draws under them
+        float x[T][8];
+        uint32_t rw[T][4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, e0 + j) : 0.0f;
-        uint32_t rw[4];
-        draw(rw);
-        replace_nan(x);
-        word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab)
-                          : encode_group<BITS, TQ_GRID_UNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab);
+        for (int t = 0; t < T; ++t) load_group<DTYPE>(g, gbase + (uint64_t)t * kTile + (uint64_t)threadIdx.x * kGroup, x[t]);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            draw(gbase + (uint64_t)t * kTile, rw[t]);
+            asm volatile("" : "+v"(rw[t][0]));                 // computed here, under the loads
+        }
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            replace_nan(x[t]);
+            const uint32_t word =
+                nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x[t], rw[t], 8, alpha, inv_step, lv, tab)
+                           : encode_group<BITS, TQ_GRID_UNIFORM, false>(x[t], rw[t], 8, alpha, inv_step, lv, tab);
+            store_codes<BITS>(payload + (((gbase + (uint64_t)t * kTile) >> 3) + threadIdx.x) * (uint64_t)BITS, word);
+        }
+        return;
     }
 
-    uint8_t* out = payload + byte_off;
-    if constexpr (BITS == 4) {
-        *reinterpret_cast<uint32_t*>(out) = word;
-    } else if constexpr (BITS == 2) {
-        *reinterpret_cast<uint16_t*>(out) = (uint16_t)word;
-    } else {
-        out[0] = (uint8_t)word;
-        out[1] = (uint8_t)(word >> 8);
-        out[2] = (uint8_t)(word >> 16);
+    // the last workgroup of a bucket: tile by tile, lanes past the end idle, the tensor's
+    // ragged last group element by element
+    for (int t = 0; t < T; ++t) {
+        const uint64_t ebase = gbase + (uint64_t)t * kTile;
+        const uint64_t e0 = ebase + (uint64_t)threadIdx.x * kGroup;
+        const uint64_t byte_off = ((ebase >> 3) + threadIdx.x) * (uint64_t)BITS;
+        if (e0 >= bend || byte_off >= payload_bytes) continue;
+        uint32_t word = 0;                                     // groups wholly in the padding encode as 0
+        if (e0 + kGroup <= d) {
+            float x[8];
+            load_group<DTYPE>(g, e0, x);
+            uint32_t rw[4];
+            draw(ebase, rw);
+            replace_nan(x);
+            word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab)
+                              : encode_group<BITS, TQ_GRID_UNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab);
+        } else if (e0 < d) {
+            const int n_valid = (int)(d - e0);
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, e0 + j) : 0.0f;
+            uint32_t rw[4];
+            draw(ebase, rw);
+            replace_nan(x);
+            word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab)
+                              : encode_group<BITS, TQ_GRID_UNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab);
+        }
+        store_codes<BITS>(payload + byte_off, word, payload_bytes - byte_off);
     }
 }
 
@@ -216,8 +262,8 @@ hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64
     const uint64_t d_pad = (d + 127) / 128 * 128;
     const uint64_t be = bucket_elems ? bucket_elems : d_pad;
     const uint64_t nb = (d_pad + be - 1) / be;
-    const uint64_t tpb = (be + tq::kTile - 1) / tq::kTile;
-    const uint64_t nblocks = nb * tpb;
+    const uint64_t tpb = ((be + tq::kTile - 1) / tq::kTile + tq::kCompressTiles - 1) / tq::kCompressTiles;
+    const uint64_t nblocks = nb * tpb;                                 // tpb = workgroups per bucket
     if (nblocks == 0 || nblocks > 0x7FFFFFFFull || count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
     const uint64_t pbytes = tq_payload_bytes(d, bits);
     tq::PtrTable gt{}, pt{};

@@ -85,6 +85,22 @@ def test_hand_made_asymmetric_codebook():
     assert (got == O.compress(g_np, P2, 1, 1, 1)).all()
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("d", [1, 5, 40, 41, 42, 43, 85, 86, 127, 128, 129, 2049, 4096 + 41])
+def test_nothing_is_written_past_the_payload(bits, d):
+    """The 3-byte groups of b = 3 can straddle the end of a short payload; the bytes behind
+    the payload (here: a guard region of the same allocation) must stay untouched."""
+    g_dev, g_np = small_gradient("cfg1", 0, d)
+    P = oracle_params(g_np, bits, B.GRID_UNIFORM)
+    nbytes = B.payload_bytes(d, bits)
+    buf = torch.full((nbytes + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+    B.tq_compress(g_dev, B.params_from_numpy(P), buf[:nbytes], bits, 77, 0, 0)
+    torch.cuda.synchronize()
+    got = buf.cpu().numpy()
+    assert (got[nbytes:] == 0xA5).all()
+    assert (got[:nbytes] == O.compress(g_np, P, 77, 0, 0)).all()
+
+
 def test_determinism_same_call_twice():
     g_dev, g_np = small_gradient("cfg2", 3, 200_000)
     P = oracle_params(g_np, 4, B.GRID_UNIFORM)
