@@ -12,7 +12,7 @@ from . import build as _build
 
 NBINS = 898
 F32, BF16 = 0, 1
-GRID_UNIFORM, GRID_NONUNIFORM = 0, 1
+GRID_UNIFORM, GRID_NONUNIFORM, GRID_BISCALED = 0, 1, 2
 
 STATS_DTYPE = np.dtype([
     ("hist", np.uint32, (NBINS,)),

@@ -13,6 +13,12 @@ Parameter Design") fed by the per-bucket statistics of ``tq_oracle.c``:
 * truncation threshold, non-uniform grid (Sec. IV-B, second boxed equation):
       same form with Q_N(alpha) = [int_{-alpha}^{alpha} p^(1/3) (1/(2 alpha))^(2/3)]^3
 * uniform codebook (Sec. IV-A):  l_k = -alpha + k * 2 alpha / s
+* truncated BiScaled quantizer (appendix "Truncated BiScaled Quantization"): two uniform
+  regions, s_beta cells on [-beta, beta] and s_alpha on the rest of [-alpha, alpha],
+      Q_B(alpha, k) = [(2 int_{k alpha}^{alpha} p)^(1/3) (1-k)^(2/3) + (2 int_0^{k alpha} p)^(1/3) k^(2/3)]^3,
+      k* = argmin_k Q_B(alpha, k),  alpha from the boxed equation with Q_B(alpha, k*),
+      s_beta / s = p1^(1/3) k / (p2^(1/3) (1-k) + p1^(1/3) k),  s_alpha = s - s_beta,
+  p1, p2 the average densities on [0, beta] and [beta, alpha], k = beta / alpha
 
 Readings where the paper is silent (each also listed in the design document):
 
@@ -29,10 +35,16 @@ Readings where the paper is silent (each also listed in the design document):
   beyond max|g| is clamped there ("no truncation"), below g_min to g_min.
 * density -> codebook: level l_k is where the integral of lambda_s from -alpha
   reaches k (so that int lambda_s = s, Sec. III-A), mirrored about zero.
+* BiScaled: k is searched over k = 0 and the histogram's bin edges below alpha
+  (beta = k alpha is then an edge), the smallest k winning a tie; the boxed
+  equation is iterated like the other two with Q = min_k Q_B(alpha, k), k* re-chosen
+  at every iterate; s_beta is the odd integer nearest to its real-valued formula,
+  within [1, s - 2] (s is odd, so an odd inner count leaves the two outer regions
+  the same even share); k* = 0 means a uniform codebook.
 """
 import numpy as np
 
-from .binding import GRID_NONUNIFORM, GRID_UNIFORM, NBINS, PARAMS_DTYPE
+from .binding import GRID_BISCALED, GRID_NONUNIFORM, GRID_UNIFORM, NBINS, PARAMS_DTYPE
 
 FLAG_ALPHA_CLAMPED_MAX = 1    # fixed point at or beyond max|g|: alpha = max|g|
 FLAG_GAMMA_CLAMPED = 2        # tail-index estimate below 2.02, lifted
@@ -88,6 +100,25 @@ class Density:
     def Q_N(self, alpha):
         return (2.0 * self.half_int_p13(alpha)) ** 3 / (2.0 * alpha) ** 2
 
+    def Q_B(self, alpha, k):
+        """Q_B(alpha, k) of the BiScaled appendix, for any 0 <= k <= 1."""
+        c_a = self.Q_U(alpha)                       # 2 int_0^alpha p
+        c_b = self.Q_U(k * alpha)                   # 2 int_0^{k alpha} p
+        outer = max(c_a - c_b, 0.0)
+        return (np.cbrt(outer) * (1.0 - k) ** (2.0 / 3.0) + np.cbrt(c_b) * k ** (2.0 / 3.0)) ** 3
+
+    def best_k(self, alpha):
+        """(j, Q_B(alpha, lo_j / alpha)) minimising Q_B over beta in {0} U {bin edges lo_j < alpha};
+        j = 0 stands for beta = 0.  The smallest beta wins a tie."""
+        best_j, best_q = 0, self.Q_B(alpha, 0.0)
+        for j in range(1, NBINS):
+            if self.lo[j] >= alpha:
+                break
+            q = self.Q_B(alpha, self.lo[j] / alpha)
+            if q < best_q:
+                best_j, best_q = j, q
+        return best_j, best_q
+
     def inv_half_int_p13(self, t):
         """Smallest x >= 0 with H(x) >= t."""
         acc = 0.0
@@ -125,7 +156,13 @@ def estimate_tail(stats, dens):
 def solve_alpha(dens, g_min, gamma, rho, s, grid):
     """Fixed point of the boxed alpha equation (uniform: Q_U, non-uniform: Q_N)."""
     flags = 0
-    Q = dens.Q_U if grid == GRID_UNIFORM else dens.Q_N
+    if grid == GRID_UNIFORM:
+        Q = dens.Q_U
+    elif grid == GRID_NONUNIFORM:
+        Q = dens.Q_N
+    else:
+        def Q(a):
+            return dens.best_k(a)[1]
     a_min = g_min * (1.0 + 2.0 ** -10)
     a_max = dens.absmax
     C = 2.0 * rho * s * s / (gamma - 2.0)
@@ -170,6 +207,40 @@ def nonuniform_levels(dens, alpha_f, s):
     return lv.astype(np.float32)
 
 
+def biscaled_split(dens, alpha_f, s):
+    """(beta, s_beta) of the BiScaled codebook at threshold alpha_f; beta = 0: uniform."""
+    a = float(alpha_f)
+    j, _ = dens.best_k(a)
+    if j == 0:
+        return 0.0, s
+    beta = dens.lo[j]
+    k = beta / a
+    c_b, c_a = dens.Q_U(beta), dens.Q_U(a)
+    p1 = c_b / (2.0 * beta)                         # average density on [0, beta]
+    p2 = max(c_a - c_b, 0.0) / (2.0 * (a - beta))   # and on [beta, alpha]
+    inner, outer = np.cbrt(p1) * k, np.cbrt(p2) * (1.0 - k)
+    x = s * inner / (inner + outer) if inner + outer > 0.0 else float(s)
+    s_beta = 2 * int(np.floor((x - 1.0) / 2.0 + 0.5)) + 1      # nearest odd integer
+    return beta, min(max(s_beta, 1), s - 2)
+
+
+def biscaled_levels(dens, alpha_f, s):
+    a = float(alpha_f)
+    beta, s_beta = biscaled_split(dens, alpha_f, s)
+    if beta <= 0.0:
+        return uniform_levels(alpha_f, s)
+    half_outer = (s - s_beta) // 2                  # cells on each side beyond beta
+    lv = np.zeros(s + 1)
+    for j in range(s_beta + 1):
+        lv[half_outer + j] = -beta + j * (2.0 * beta / s_beta)
+    lv[half_outer], lv[half_outer + s_beta] = -beta, beta
+    for j in range(1, half_outer + 1):
+        x = beta + j * ((a - beta) / half_outer)
+        lv[half_outer + s_beta + j], lv[half_outer - j] = x, -x
+    lv[0], lv[s] = -a, a
+    return lv.astype(np.float32)
+
+
 def tq_params_one(stats, bits, grid, alpha_override=0.0):
     """One PARAMS_DTYPE record from one STATS_DTYPE record.
 
@@ -207,8 +278,10 @@ def tq_params_one(stats, bits, grid, alpha_override=0.0):
     alpha_f = np.float32(max(alpha, ALPHA_FLOOR))
     if grid == GRID_UNIFORM or dens.half_int_p13(float(alpha_f)) <= 0.0:
         lv = uniform_levels(alpha_f, s)      # (no mass inside [-alpha, alpha]: nothing to shape)
-    else:
+    elif grid == GRID_NONUNIFORM:
         lv = nonuniform_levels(dens, alpha_f, s)
+    else:
+        lv = biscaled_levels(dens, alpha_f, s)
     inv_w = np.zeros(16, dtype=np.float32)
     if grid == GRID_UNIFORM:
         inv_w[:s] = np.float32(s / (2.0 * float(alpha_f)))

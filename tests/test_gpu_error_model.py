@@ -47,7 +47,7 @@ def dev():
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("grid", [0, 1])
+@pytest.mark.parametrize("grid", [0, 1, 2])
 def test_round_trip_error_is_the_expected_one(dev, bits, grid):
     P, mse = dev.roundtrip_mse(bits, grid)
     assert abs(mse / expected_mse(dev.g_np, P) - 1.0) < 0.01
@@ -61,16 +61,23 @@ def test_model_of_sec_4a_bounds_the_uniform_error(dev, bits):
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("grid", [0, 1])
+@pytest.mark.parametrize("grid", [0, 1, 2])
 def test_truncation_helps_and_formula_alpha_is_near_the_best(dev, bits, grid):
     P, mse = dev.roundtrip_mse(bits, grid)
     _, no_trunc = dev.roundtrip_mse(bits, grid, -1.0)                  # alpha = max|g|
     assert mse < no_trunc / (20.0 if grid == 0 else 1.0)
     a = float(P["alpha"][0])
     sweep = [dev.roundtrip_mse(bits, grid, a * f)[1] for f in SWEEP]
-    assert mse <= 1.2 * min(sweep)
+    # the appendix calls the BiScaled alpha a one-step approximation: a wider margin there
+    assert mse <= (1.2 if grid < 2 else 1.4) * min(sweep)
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
 def test_nonuniform_codebook_beats_uniform(dev, bits):
     assert dev.roundtrip_mse(bits, 1)[1] < dev.roundtrip_mse(bits, 0)[1]
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_biscaled_codebook_beats_uniform(dev, bits):
+    """The closing claim of the BiScaled appendix."""
+    assert dev.roundtrip_mse(bits, 2)[1] < dev.roundtrip_mse(bits, 0)[1]

@@ -26,7 +26,7 @@ def roundtrip_mse(g, P, bits):
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("grid", [0, 1])
+@pytest.mark.parametrize("grid", [0, 1, 2])
 def test_empirical_error_is_the_expected_one(sample, bits, grid):
     g, S = sample
     P = OP.tq_params(S, bits, grid)
@@ -42,7 +42,7 @@ def test_model_of_sec_4a_bounds_the_uniform_error(sample, bits):
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("grid", [0, 1])
+@pytest.mark.parametrize("grid", [0, 1, 2])
 def test_truncation_helps_and_formula_alpha_is_near_the_best(sample, bits, grid):
     g, S = sample
     P = OP.tq_params(S, bits, grid)
@@ -52,10 +52,18 @@ def test_truncation_helps_and_formula_alpha_is_near_the_best(sample, bits, grid)
     assert e < no_trunc / (20.0 if grid == 0 else 1.0)
     a = float(P["alpha"][0])
     sweep = [expected_mse(g, OP.tq_params(S, bits, grid, a * f)) for f in SWEEP]
-    assert e <= 1.2 * min(sweep)
+    # the appendix calls the BiScaled alpha a one-step approximation: a wider margin there
+    assert e <= (1.2 if grid < 2 else 1.4) * min(sweep)
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
 def test_nonuniform_codebook_beats_uniform(sample, bits):
     g, S = sample
     assert expected_mse(g, OP.tq_params(S, bits, 1)) < expected_mse(g, OP.tq_params(S, bits, 0))
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_biscaled_codebook_beats_uniform(sample, bits):
+    """The closing claim of the BiScaled appendix."""
+    g, S = sample
+    assert expected_mse(g, OP.tq_params(S, bits, 2)) < expected_mse(g, OP.tq_params(S, bits, 0))
