@@ -34,7 +34,7 @@ extern "C" {
 
 enum { TQ_OK = 0, TQ_EINVAL = 1, TQ_EALIGN = 2, TQ_EUNSUPPORTED = 3, TQ_EHIP = 4 };
 enum { TQ_F32 = 0, TQ_BF16 = 1 };                      /* gradient dtype */
-enum { TQ_GRID_UNIFORM = 0, TQ_GRID_NONUNIFORM = 1 };  /* codebook family */
+enum { TQ_GRID_UNIFORM = 0, TQ_GRID_NONUNIFORM = 1, TQ_GRID_BISCALED = 2 };  /* codebook family */
 
 #define TQ_NBINS 898        /* histogram bins of |g|, see tq_stats */
 #define TQ_MAX_WORKERS 64   /* largest N of tq_decompress_aggregate */
@@ -102,7 +102,12 @@ int tq_stats(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
  * truncation threshold alpha by the fixed point of the boxed equation of
  * Sec. IV-A (uniform grid, Q_U) or Sec. IV-B (non-uniform grid, Q_N), and the
  * codebook: l_k = -alpha + k 2alpha/s, or the levels at which the integral of
- * lambda_s ~ p^(1/3) (Sec. IV-B, first boxed equation) reaches k.  p inside
+ * lambda_s ~ p^(1/3) (Sec. IV-B, first boxed equation) reaches k.  TQ_GRID_BISCALED is
+ * the truncated BiScaled quantizer of the appendix: alpha from the same boxed form with
+ * Q_B(alpha, k*), k* = argmin_k Q_B searched over k = 0 and the histogram's bin edges
+ * below alpha, s_beta (odd, nearest to the appendix's formula) uniform cells on
+ * [-k* alpha, k* alpha] and s - s_beta on the rest; tq_compress and the server calls treat
+ * it like any non-uniform codebook.  p inside
  * [-alpha, alpha] is the histogram's density; gamma, rho come from the tail
  * terms of tq_stats or, without g_min, from the bins above the 0.9-quantile.
  *   stats_dev       [nb] from tq_stats

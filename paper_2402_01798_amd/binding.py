@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libtq.so")
 
 OK, EINVAL, EALIGN, EUNSUPPORTED, EHIP = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
-GRID_UNIFORM, GRID_NONUNIFORM = 0, 1
+GRID_UNIFORM, GRID_NONUNIFORM, GRID_BISCALED = 0, 1, 2
 NBINS = 898
 MAX_WORKERS = 64
 STATS_BYTES = 3632

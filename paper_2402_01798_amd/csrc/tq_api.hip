@@ -90,7 +90,7 @@ int tq_params_multi(const tq_stats_t* const* stats_host, int count, uint64_t nb,
 {
     int rc;
     if ((rc = check_bits(bits))) return rc;
-    if (grid != TQ_GRID_UNIFORM && grid != TQ_GRID_NONUNIFORM) return TQ_EINVAL;
+    if (grid != TQ_GRID_UNIFORM && grid != TQ_GRID_NONUNIFORM && grid != TQ_GRID_BISCALED) return TQ_EINVAL;
     if (nb == 0 || count < 1 || !stats_host || !params_host) return TQ_EINVAL;
     if (count > TQ_MAX_WORKERS) return TQ_EUNSUPPORTED;
     if (alpha_override != alpha_override || alpha_override > 3.0e38f) return TQ_EINVAL;

@@ -7,13 +7,20 @@
 //                   Q = Q_U (Sec. IV-A, boxed) or Q_N (Sec. IV-B, second boxed equation)
 //   codebook        uniform: l_k = -alpha + k 2alpha/s; non-uniform: the points where the
 //                   integral of lambda_s ~ p^(1/3) (Sec. IV-B, first boxed equation) reaches k
+//   BiScaled        (appendix "Truncated BiScaled Quantization") Q = min_k Q_B(alpha, k),
+//                   Q_B = [(2 int_{k alpha}^{alpha} p)^(1/3) (1-k)^(2/3) + (2 int_0^{k alpha} p)^(1/3) k^(2/3)]^3,
+//                   k over 0 and the bin edges below alpha; s_beta = the odd integer nearest to
+//                   s p1^(1/3) k / (p2^(1/3) (1-k) + p1^(1/3) k) uniform cells on [-k alpha, k alpha],
+//                   the other s - s_beta on the rest of [-alpha, alpha]
 //
 // The density p on [-alpha, alpha] is the histogram's (constant inside a bin).  With the
 // prefix sums cum[i] = #{|g| below bin i} and H[i] = int_0^{lo_i} p^(1/3), both Q_U(alpha)
 // and the integral of p^(1/3) up to alpha cost O(1) per evaluation.  The per-bin cube roots
 // and logarithms and the two prefix sums are computed by all lanes (4 bins per lane, a
 // wavefront scan, a 4-entry carry through LDS); only the fixed-point iteration itself, a
-// chain of dependent scalar steps, runs on lane 0.
+// chain of dependent scalar steps, runs on lane 0.  For the BiScaled family every step of that
+// chain holds a minimum over up to 898 candidate k: there all lanes walk the chain together
+// (each computing the same scalars) and share the search, 4 candidates per lane.
 #include "tq_device.h"
 
 namespace tq {
@@ -57,6 +64,8 @@ struct ParamsLds {
     double carry[4];       // per-wavefront totals of the scan in flight
     double total;
     int tail_bin;
+    double best_q[4];      // per-wavefront minimum of the BiScaled search and the bin it belongs to
+    int best_j[4];
 };
 
 // Exclusive prefix sum over the 1024 (lane, slot) values v[0..3] of all 256 lanes, in bin
@@ -206,9 +215,65 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_
     (void)excl_t;
     __syncthreads();
     const double sum_log_binned = L.total;
-    if (tid != 0) return;
+    const bool biscaled = grid == TQ_GRID_BISCALED;
+    if (!biscaled && tid != 0) return;                    // BiScaled: all lanes stay, in lockstep
 
     const DensityView D{L, n, n > 0.0 ? 1.0 / n : 0.0, absmax};
+
+    // BiScaled search, collective: the edge lo_j < a (j = 0: beta = 0) that minimises Q_B(a, lo_j / a),
+    // the smallest such edge on a tie; returns Q_B and leaves the bin in best_bin.  Each lane keeps,
+    // for its 4 bins, the parts that do not depend on a: (mass below the edge)^(1/3), edge^(2/3).
+    double cb13[kBinsPerLane], lo23[kBinsPerLane], lo_e[kBinsPerLane], cb[kBinsPerLane];
+    if (biscaled) {
+#pragma unroll
+        for (int k = 0; k < kBinsPerLane; ++k) {
+            const int j = i0 + k;
+            lo_e[k] = j < kNB ? bin_lo(j) : 0.0;
+            cb[k] = j < kNB ? L.cum[j] * D.inv_n : 0.0;
+            cb13[k] = cbrt(cb[k]);
+            lo23[k] = cbrt(lo_e[k] * lo_e[k]);
+        }
+    }
+    int best_bin = 0;
+    auto biscaled_min = [&](double a) -> double {
+        const double c_a = D.Q_U(a);
+        const double inv_a = 1.0 / a, inv_a23 = 1.0 / cbrt(a * a);
+        double q = 1.0e300;
+        int jbest = kNB;
+#pragma unroll
+        for (int k = 0; k < kBinsPerLane; ++k) {
+            const int j = i0 + k;
+            if (j < kNB && (j == 0 || lo_e[k] < a)) {
+                const double kk = lo_e[k] * inv_a;
+                double outer = c_a - cb[k];
+                outer = outer > 0.0 ? outer : 0.0;
+                const double r = 1.0 - kk;
+                const double v = cbrt(outer) * cbrt(r * r) + cb13[k] * (lo23[k] * inv_a23);
+                if (v < q) { q = v; jbest = j; }          // ascending j: the first minimum stays
+            }
+        }
+        const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const double oq = __shfl_xor(q, off, 64);
+            const int oj = __shfl_xor(jbest, off, 64);
+            if (oq < q || (oq == q && oj < jbest)) { q = oq; jbest = oj; }
+        }
+        __syncthreads();                                   // the previous search has been read
+        if (lane == 0) { L.best_q[wave] = q; L.best_j[wave] = jbest; }
+        __syncthreads();
+        q = L.best_q[0];
+        jbest = L.best_j[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const double oq = L.best_q[w];
+            const int oj = L.best_j[w];
+            if (oq < q || (oq == q && oj < jbest)) { q = oq; jbest = oj; }
+        }
+        best_bin = jbest;
+        return q * q * q;
+    };
+
     const int s = (1 << bits) - 1;
     uint32_t flags = 0;
     double gamma = 0.0, rho = 0.0, alpha;
@@ -247,7 +312,7 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_
             double a = clampa(g_min * exp(ex * log_c));    // alpha' of Sec. IV-A (Q = 1)
             bool converged = false;
             for (int it = 0; it < kMaxIter; ++it) {
-                const double q = grid == TQ_GRID_UNIFORM ? D.Q_U(a) : D.Q_N(a);
+                const double q = grid == TQ_GRID_UNIFORM ? D.Q_U(a) : (biscaled ? biscaled_min(a) : D.Q_N(a));
                 // (C/q)^ex evaluated as exp(ex (ln C - ln q))
                 const double an = q > 0.0 ? clampa(g_min * exp(ex * (log_c - log(q)))) : a_max;
                 const bool done = fabs(an - a) <= kRelTol * an;
@@ -264,11 +329,36 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_
     tq_params_t* P = params + blockIdx.x;
     const float alpha_f = (float)(alpha > kAlphaFloor ? alpha : kAlphaFloor);
     const double af = (double)alpha_f;
+    const double half = D.half_int(af);
+    if (biscaled) {
+        if (half > 0.0) (void)biscaled_min(af);            // the split belongs to the rounded threshold
+        if (tid != 0) return;
+    }
     float lv[16];
     for (int k = 0; k < 16; ++k) lv[k] = 0.0f;
-    const double half = D.half_int(af);
-    if (grid == TQ_GRID_UNIFORM || !(half > 0.0)) {
+    if (grid == TQ_GRID_UNIFORM || !(half > 0.0) || (biscaled && best_bin == 0)) {
         for (int k = 0; k <= s; ++k) lv[k] = (float)(-af + (double)k * (2.0 * af / (double)s));
+        lv[s] = alpha_f;
+    } else if (biscaled) {
+        const double beta = bin_lo(best_bin), kk = beta / af;
+        const double c_b = L.cum[best_bin] * D.inv_n, c_a = D.Q_U(af);
+        const double p1 = c_b / (2.0 * beta);
+        const double rest = c_a - c_b > 0.0 ? c_a - c_b : 0.0;
+        const double p2 = rest / (2.0 * (af - beta));
+        const double inner = cbrt(p1) * kk, outer = cbrt(p2) * (1.0 - kk);
+        const double x = inner + outer > 0.0 ? (double)s * inner / (inner + outer) : (double)s;
+        int s_beta = 2 * (int)floor((x - 1.0) * 0.5 + 0.5) + 1;           // nearest odd integer
+        s_beta = s_beta < 1 ? 1 : (s_beta > s - 2 ? s - 2 : s_beta);
+        const int h = (s - s_beta) / 2;                                    // cells beyond beta on each side
+        for (int j = 0; j <= s_beta; ++j) lv[h + j] = (float)(-beta + (double)j * (2.0 * beta / (double)s_beta));
+        lv[h] = (float)(-beta);
+        lv[h + s_beta] = (float)beta;
+        for (int j = 1; j <= h; ++j) {
+            const double xo = beta + (double)j * ((af - beta) / (double)h);
+            lv[h + s_beta + j] = (float)xo;
+            lv[h - j] = -(float)xo;
+        }
+        lv[0] = -alpha_f;
         lv[s] = alpha_f;
     } else {
         lv[0] = -alpha_f;

@@ -65,6 +65,32 @@ def test_whole_path_matches_oracle(name, d):
             assert (got_out == want_out).all()
 
 
+@pytest.mark.parametrize("name,d,bits", [("cfg1", None, 3), ("cfg4", (2 << 20) + 777, 2), ("cfg2", 200_000, 4)])
+def test_whole_path_with_the_biscaled_codebook(name, d, bits):
+    """The BiScaled quantizer of the appendix through the whole path: parameters at 1e-6,
+    then codes and averages bit for bit with the parameter bytes the device produced."""
+    wl = synth.WORKLOADS[name]
+    d = wl.d if d is None else d
+    N = 3
+    gs = [synth.make_gradient(wl, i, "cpu", d) for i in range(N)]
+    stats, params, pays, out = run_device(wl, [g.cuda() for g in gs], bits, B.GRID_BISCALED, seed=99, step=4)
+    P_dev, pay_or = [], []
+    for i in range(N):
+        g_np = synth.as_numpy(gs[i])
+        S_or = O.stats(g_np, bucket_elems=wl.bucket_elems, g_min=wl.g_min)
+        P_or = OP.tq_params(S_or, bits, B.GRID_BISCALED)
+        Pd = B.params_to_numpy(params[i]).view(O.PARAMS_DTYPE)
+        assert np.allclose(Pd["alpha"], P_or["alpha"], rtol=1e-6)
+        assert np.allclose(Pd["level"], P_or["level"], rtol=1e-6, atol=0)
+        assert (Pd["flags"] == P_or["flags"]).all() and (Pd["grid"] == B.GRID_BISCALED).all()
+        want = O.compress(g_np, Pd, 99, i, 4, bucket_elems=wl.bucket_elems)
+        assert (pays[i].cpu().numpy() == want).all()
+        P_dev.append(Pd)
+        pay_or.append(want)
+    want_out = O.decompress_aggregate(pay_or, P_dev, d, bits, bucket_elems=wl.bucket_elems)
+    assert (out.cpu().numpy() == want_out).all()
+
+
 def test_cfg2_full_size_full_arrays():
     """BASELINE config 2 at its full size (11.2 M x 8 workers, uniform 2- and 4-bit), in the
     launch configuration the benchmark times; every byte and every average is compared."""

@@ -68,7 +68,7 @@ def assert_params_close(got, want):
 
 @pytest.mark.parametrize("wl,g_min", PARAM_CASES)
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("grid", [B.GRID_UNIFORM, B.GRID_NONUNIFORM])
+@pytest.mark.parametrize("grid", [B.GRID_UNIFORM, B.GRID_NONUNIFORM, B.GRID_BISCALED])
 def test_params_match_oracle(wl, g_min, bits, grid):
     d, bucket = 300_000, 65_536
     g_dev, g_np = small_gradient(wl, 0, d)
@@ -87,7 +87,7 @@ def test_params_override_and_degenerate(override):
     d = 50_000
     g_dev, g_np = small_gradient("cfg1", 0, d)
     st = device_stats(g_dev, 0, 1e-4)
-    for grid in (B.GRID_UNIFORM, B.GRID_NONUNIFORM):
+    for grid in (B.GRID_UNIFORM, B.GRID_NONUNIFORM, B.GRID_BISCALED):
         pr = B.alloc_params(d)
         B.tq_params(st, pr, 3, grid, override)
         torch.cuda.synchronize()
@@ -96,7 +96,7 @@ def test_params_override_and_degenerate(override):
     for data in (torch.zeros(4096, device="cuda"), torch.full((4096,), 0.25, device="cuda"),
                  torch.full((4096,), float("nan"), device="cuda")):
         st = device_stats(data)
-        for grid in (B.GRID_UNIFORM, B.GRID_NONUNIFORM):
+        for grid in (B.GRID_UNIFORM, B.GRID_NONUNIFORM, B.GRID_BISCALED):
             pr = B.alloc_params(4096)
             B.tq_params(st, pr, 2, grid)
             torch.cuda.synchronize()
