@@ -81,7 +81,8 @@ uint64_t tq_payload_bytes(uint64_t d, int bits);
  * tq_stats -- the reductions the parameter design consumes (Sec. IV-A: tail
  * mass rho and Q_U(alpha); Sec. IV-B: integral of p^(1/3); Sec. V: the two
  * terms of the maximum-likelihood tail index gamma = 1 + n/sum ln(g_j/g_min)).
- *   g_dev      [d] gradient, TQ_F32 (float) or TQ_BF16 (uint16 bit patterns)
+ *   g_dev      [d] gradient, TQ_F32 (float) or TQ_BF16 (uint16 bit patterns); a bucket
+ *              holds fewer than 2^32 elements (32-bit counts), else TQ_EUNSUPPORTED
  *   g_min      > 0: also count and log-sum the elements with |g| > g_min
  *              (must be >= 2^-40); <= 0: leave the tail to tq_params
  *   stats_dev  [tq_num_buckets] written in full; deterministic

@@ -67,6 +67,8 @@ int tq_stats_multi(const void* const* g_host, int count, int dtype, uint64_t d, 
     if ((rc = check_layout(d, bucket_elems)) || (rc = check_dtype(dtype))) return rc;
     if (count < 1 || !g_host || !stats_host || !workspace_dev) return TQ_EINVAL;
     if (count > TQ_MAX_WORKERS) return TQ_EUNSUPPORTED;
+    // the counts of tq_stats_t are 32-bit: one bucket holds fewer than 2^32 elements
+    if ((bucket_elems ? (bucket_elems < d ? bucket_elems : d) : d) > 0xFFFFFFFFull) return TQ_EUNSUPPORTED;
     if (workspace_bytes < (uint64_t)count * tq_stats_workspace_bytes_impl(d, bucket_elems)) return TQ_EINVAL;
     if (g_min != g_min || (g_min > 0.0f && g_min < 9.094947017729282e-13f) || g_min > 3.0e38f) return TQ_EINVAL;
     if (!aligned16(workspace_dev)) return TQ_EALIGN;

@@ -68,6 +68,8 @@ def test_bad_arguments_are_rejected_without_a_device(L):
     assert L.tq_stats(p, 0, 1000, 0, 0.0, p, p, 16, None) == B.EINVAL          # workspace too small
     assert L.tq_stats(p, 0, 1000, 0, 0.0, p, None, 1 << 30, None) == B.EINVAL  # no workspace
     assert L.tq_stats(None, 0, 1000, 0, 0.0, p, p, 1 << 30, None) == B.EINVAL
+    assert L.tq_stats(p, 0, 1 << 32, 0, 0.0, p, p, 1 << 30, None) == B.EUNSUPPORTED    # 32-bit counts
+    assert L.tq_stats(p, 0, 1 << 33, 1 << 32, 0.0, p, p, 1 << 30, None) == B.EUNSUPPORTED
     assert L.tq_params(p, 1, 5, 0, 0.0, p, None) == B.EINVAL                 # bits
     assert L.tq_params(p, 1, 3, 3, 0.0, p, None) == B.EINVAL                 # grid
     assert L.tq_params(p, 0, 3, 0, 0.0, p, None) == B.EINVAL                 # no buckets
