@@ -198,6 +198,20 @@ int tq_decompress_aggregate_update(const void* const* payload_host,
                                    float momentum, float weight_decay, float* theta_dev,
                                    float* velocity_dev, void* stream);
 
+/*
+ * tq_quantize_dequantize -- out[e] = Q[T_alpha(g[e])] (Eq. 1, Eq. 2) as float values: what the
+ * server reconstructs from this worker's message, computed without producing the message.
+ * Same draws and arithmetic as tq_compress, so the result equals, bit for bit, what
+ * tq_decompress_aggregate returns for N = 1 from tq_compress's payload.  For studies of
+ * training under quantization (the experiments of Sec. V) that do not need the wire format.
+ *   arguments as in tq_compress; accumulate 0: out = value, 1: out += value
+ *   out_dev   [d] floats
+ */
+int tq_quantize_dequantize(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
+                           const tq_params_t* params_dev, int bits, uint64_t seed,
+                           uint32_t worker, uint32_t step, int accumulate, float* out_dev,
+                           void* stream);
+
 /* Text for a return code (static storage). */
 const char* tq_strerror(int code);
 

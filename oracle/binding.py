@@ -189,6 +189,14 @@ def decompress_aggregate_update(payloads, params, theta, bits, eta, momentum=0.0
     return theta
 
 
+def quantize_dequantize(g, params, seed, worker, step, bucket_elems=0):
+    """Q[T_alpha(g)] as values: the client step of Alg. 1 followed by the server's look-up."""
+    params = np.ascontiguousarray(params, dtype=PARAMS_DTYPE).reshape(-1)
+    bits = int(params["bits"][0])
+    return dequantize(compress(g, params, seed, worker, step, bucket_elems=bucket_elems), params, g.size, bits,
+                      bucket_elems=bucket_elems)
+
+
 def dequantize(payload, params, d, bits, bucket_elems=0):
     payload = np.ascontiguousarray(payload, dtype=np.uint8)
     params = np.ascontiguousarray(params, dtype=PARAMS_DTYPE).reshape(-1)

@@ -63,6 +63,8 @@ def lib():
         L.tq_compress.argtypes = [vp, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
         L.tq_decompress_aggregate.argtypes = [vp, vp, vp, i32, u64, u64, i32, i32, vp, vp]
         L.tq_decompress_aggregate_update.argtypes = [vp, vp, vp, i32, u64, u64, i32, f32, f32, f32, vp, vp, vp]
+        L.tq_quantize_dequantize.argtypes = [vp, i32, u64, u64, vp, i32, u64, u32, u32, i32, vp, vp]
+        L.tq_quantize_dequantize.restype = i32
         L.tq_strerror.argtypes = [i32]
         L.tq_strerror.restype = C.c_char_p
         L.tq_stats_multi.argtypes = [vp, i32, i32, u64, u64, f32, vp, vp, u64, vp]
@@ -156,6 +158,18 @@ def tq_compress(g, params, payload, bits, seed, worker, step, bucket_elems=0):
                              bits, seed, worker, step, _dev(payload, "payload"), _stream()),
            "tq_compress")
     return payload
+
+
+def tq_quantize_dequantize(g, params, out, bits, seed, worker, step, bucket_elems=0, accumulate=False):
+    d = g.numel()
+    if params.numel() != num_buckets(d, bucket_elems) * PARAMS_BYTES:
+        raise ValueError("params buffer does not match the number of buckets")
+    if out.dtype != torch.float32 or out.numel() != d:
+        raise ValueError("out must be float32 of the gradient's size")
+    _check(lib().tq_quantize_dequantize(_dev(g, "g"), _dtype_code(g), d, bucket_elems, _dev(params, "params"),
+                                        bits, seed, worker, step, int(bool(accumulate)), _dev(out, "out"),
+                                        _stream()), "tq_quantize_dequantize")
+    return out
 
 
 def _ptr_array(tensors, what):

@@ -17,6 +17,10 @@ hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const
                             int mode, float eta, float momentum, float weight_decay, float* velocity,
                             float* out, hipStream_t st);
 
+hipError_t tq_launch_simulate(const void* g, int dtype, uint64_t d, uint64_t bucket_elems, const tq_params_t* params,
+                              int bits, uint64_t seed, uint32_t worker, uint32_t step, int accumulate, float* out,
+                              hipStream_t st);
+
 static_assert(sizeof(tq_stats_t) == 3632, "tq_stats_t layout is part of the interface");
 static_assert(sizeof(tq_params_t) == 160, "tq_params_t layout is part of the interface");
 
@@ -132,6 +136,18 @@ int tq_compress(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
 {
     return tq_compress_multi(&g_dev, 1, dtype, d, bucket_elems, &params_dev, bits, seed, worker, step,
                              &payload_dev, stream);
+}
+
+int tq_quantize_dequantize(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
+                           const tq_params_t* params_dev, int bits, uint64_t seed, uint32_t worker, uint32_t step,
+                           int accumulate, float* out_dev, void* stream)
+{
+    int rc;
+    if ((rc = check_layout(d, bucket_elems)) || (rc = check_dtype(dtype)) || (rc = check_bits(bits))) return rc;
+    if (!g_dev || !params_dev || !out_dev) return TQ_EINVAL;
+    if (!aligned16(g_dev) || !aligned16(params_dev) || !aligned16(out_dev)) return TQ_EALIGN;
+    return from_hip(tq_launch_simulate(g_dev, dtype, d, bucket_elems, params_dev, bits, seed, worker, step,
+                                       accumulate ? 1 : 0, out_dev, static_cast<hipStream_t>(stream)));
 }
 
 // Checks shared by the two server-side calls.

@@ -223,6 +223,75 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     }
 }
 
+// tq_quantize_dequantize: out[e] = Q[T_alpha(g[e])] as the server would reconstruct it from
+// this worker's message (the level of the code tq_compress_kernel would have written: same
+// draws, same arithmetic), without the round trip through a payload.  One tile per workgroup.
+template <int DTYPE, int BITS, bool ACC>
+__global__ __launch_bounds__(kBlock) void tq_simulate_kernel(
+    const void* __restrict__ g, uint64_t d, uint64_t d_pad, uint64_t bucket_elems, uint32_t tiles_per_bucket,
+    const tq_params_t* __restrict__ params, uint32_t seed_lo, uint32_t seed_hi, uint32_t worker, uint32_t step,
+    float* __restrict__ out)
+{
+    constexpr uint32_t S = (1u << BITS) - 1u;
+    const TileGeom t = tile_geom(blockIdx.x, d_pad, bucket_elems, tiles_per_bucket);
+    const uint64_t bend = t.eend < d ? t.eend : d;
+    if (t.ebase >= bend) return;
+    const tq_params_t* P = params + t.bucket;
+
+    __shared__ LevelLds tab;                                   // levels for the look-up of both families
+    float lv[16];
+    const float alpha = P->alpha;
+    const float inv_step = P->inv_w[0];
+    const bool nonuniform = P->grid != TQ_GRID_UNIFORM;        // uniform over the workgroup
+    if (threadIdx.x < 16) tab.e[threadIdx.x] = make_float2(P->level[threadIdx.x], P->inv_w[threadIdx.x]);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) lv[j] = P->level[j];           // wave-uniform: scalar loads
+    __syncthreads();
+
+    const uint64_t e0 = t.ebase + (uint64_t)threadIdx.x * kGroup;
+    if (e0 >= bend) return;
+    const int n_valid = bend - e0 >= (uint64_t)kGroup ? kGroup : (int)(bend - e0);
+    float x[8];
+    if (n_valid == kGroup) {
+        load_group<DTYPE>(g, e0, x);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, e0 + j) : 0.0f;
+    }
+    const uint64_t q = e0 >> 3;
+    uint32_t rw[4];
+    philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), worker, step, seed_lo, seed_hi, rw);
+    replace_nan(x);
+    float y[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t r = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
+        const uint32_t code = nonuniform ? quantize<BITS, TQ_GRID_NONUNIFORM>(x[j], (float)r, alpha, inv_step, lv, tab)
+                                         : quantize<BITS, TQ_GRID_UNIFORM>(x[j], (float)r, alpha, inv_step, lv, tab);
+        y[j] = tab.e[code & S].x;
+    }
+    float* o = out + e0;
+    if (n_valid == kGroup) {
+        float4* o4 = reinterpret_cast<float4*>(o);
+        float4 a = make_float4(y[0], y[1], y[2], y[3]), b = make_float4(y[4], y[5], y[6], y[7]);
+        if constexpr (ACC) {
+            const float4 pa = o4[0], pb = o4[1];
+            a.x = pa.x + a.x; a.y = pa.y + a.y; a.z = pa.z + a.z; a.w = pa.w + a.w;
+            b.x = pb.x + b.x; b.y = pb.y + b.y; b.z = pb.z + b.z; b.w = pb.w + b.w;
+        }
+        o4[0] = a;
+        o4[1] = b;
+    } else {
+#pragma clang loop unroll(disable)
+        for (int j = 0; j < n_valid; ++j) {
+            float v = y[0];
+#pragma unroll
+            for (int k = 1; k < 8; ++k) v = (j == k) ? y[k] : v;
+            o[j] = ACC ? o[j] + v : v;
+        }
+    }
+}
+
 }  // namespace tq
 
 namespace {
@@ -273,4 +342,38 @@ hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64
     if (dtype == TQ_F32)
         return launch<TQ_F32>(bits, blocks, st, gt, d, d_pad, be, (uint32_t)tpb, pt, seed, first_worker, step, yt, pbytes);
     return launch<TQ_BF16>(bits, blocks, st, gt, d, d_pad, be, (uint32_t)tpb, pt, seed, first_worker, step, yt, pbytes);
+}
+
+// Host side of tq_quantize_dequantize after the argument checks of the C entry point.
+hipError_t tq_launch_simulate(const void* g, int dtype, uint64_t d, uint64_t bucket_elems, const tq_params_t* params,
+                              int bits, uint64_t seed, uint32_t worker, uint32_t step, int accumulate, float* out,
+                              hipStream_t st)
+{
+    const uint64_t d_pad = (d + 127) / 128 * 128;
+    const uint64_t be = bucket_elems ? bucket_elems : d_pad;
+    const uint64_t nb = (d_pad + be - 1) / be;
+    const uint64_t tpb = (be + tq::kTile - 1) / tq::kTile;
+    const uint64_t nblocks = nb * tpb;
+    if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    const uint32_t slo = (uint32_t)seed, shi = (uint32_t)(seed >> 32);
+    const dim3 blocks((unsigned)nblocks), threads(tq::kBlock);
+#define TQ_LAUNCH_SIM(DT, B)                                                                                      \
+    do {                                                                                                          \
+        if (accumulate)                                                                                           \
+            hipLaunchKernelGGL((tq::tq_simulate_kernel<DT, B, true>), blocks, threads, 0, st, g, d, d_pad, be,    \
+                               (uint32_t)tpb, params, slo, shi, worker, step, out);                               \
+        else                                                                                                      \
+            hipLaunchKernelGGL((tq::tq_simulate_kernel<DT, B, false>), blocks, threads, 0, st, g, d, d_pad, be,   \
+                               (uint32_t)tpb, params, slo, shi, worker, step, out);                               \
+    } while (0)
+#define TQ_LAUNCH_SIM_B(DT)                      \
+    switch (bits) {                              \
+        case 2: TQ_LAUNCH_SIM(DT, 2); break;     \
+        case 3: TQ_LAUNCH_SIM(DT, 3); break;     \
+        default: TQ_LAUNCH_SIM(DT, 4); break;    \
+    }
+    if (dtype == TQ_F32) { TQ_LAUNCH_SIM_B(TQ_F32) } else { TQ_LAUNCH_SIM_B(TQ_BF16) }
+#undef TQ_LAUNCH_SIM_B
+#undef TQ_LAUNCH_SIM
+    return hipGetLastError();
 }

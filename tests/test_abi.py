@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) == {"tq_num_buckets", "tq_payload_bytes", "tq_stats", "tq_stats_workspace_bytes", "tq_params",
                           "tq_compress", "tq_decompress_aggregate", "tq_decompress_aggregate_update",
-                          "tq_strerror",
+                          "tq_quantize_dequantize", "tq_strerror",
                           "tq_stats_multi", "tq_params_multi", "tq_compress_multi"}
     for n in names:
         assert getattr(L, n) is not None
@@ -81,6 +81,9 @@ def test_bad_arguments_are_rejected_without_a_device(L):
     assert L.tq_decompress_aggregate(arr, arr, None, 0, 1000, 0, 3, 0, p, None) == B.EINVAL    # N = 0
     assert L.tq_decompress_aggregate(arr, arr, None, 65, 1000, 0, 3, 0, p, None) == B.EUNSUPPORTED
     assert L.tq_decompress_aggregate(arr, arr, None, 2, 1000, 0, 3, 0, odd, None) == B.EALIGN
+    assert L.tq_quantize_dequantize(p, 0, 1000, 0, p, 6, 0, 0, 0, 0, p, None) == B.EINVAL     # bits
+    assert L.tq_quantize_dequantize(p, 0, 1000, 0, p, 3, 0, 0, 0, 0, odd, None) == B.EALIGN
+    assert L.tq_quantize_dequantize(p, 0, 1000, 0, None, 3, 0, 0, 0, 0, p, None) == B.EINVAL
     upd = L.tq_decompress_aggregate_update
     assert upd(arr, arr, None, 0, 1000, 0, 3, 0.1, 0.9, 0.0, p, None, None) == B.EINVAL      # N = 0
     assert upd(arr, arr, None, 2, 1000, 0, 5, 0.1, 0.9, 0.0, p, None, None) == B.EINVAL      # bits
