@@ -40,6 +40,7 @@ __device__ __forceinline__ uint32_t load_codes(const uint8_t* p, bool room_for_d
 
 // What happens to the aggregate g_bar of an element (the MODE of the kernels below):
 //   kStore        out = g_bar                           Alg. 1, server step "aggregate"
+//   kStoreStream  the same, stored with the non-temporal hint (small outputs, see store8)
 //   kAccumulate   out = out + g_bar
 //   kSgd          theta = theta - eta * u,  u = g_bar + weight_decay * theta
 //                                                       Alg. 1, server step "update", fused
@@ -49,7 +50,7 @@ __device__ __forceinline__ uint32_t load_codes(const uint8_t* p, bool room_for_d
 // on purpose: with a run-time flag the read-modify-write branch leaves "a load may be pending"
 // on every path, and the compiler then waits for ALL outstanding memory operations -- the
 // tile's own stores included -- before the next tile.
-enum { kStore = 0, kAccumulate = 1, kSgd = 2, kSgdMomentum = 3 };
+enum { kStore = 0, kAccumulate = 1, kSgd = 2, kSgdMomentum = 3, kStoreStream = 4 };
 
 struct Update {
     float eta, momentum, weight_decay;
@@ -59,7 +60,7 @@ struct Update {
 template <int MODE>
 __device__ __forceinline__ float finish(float g_bar, float prev, float& vel, const Update& up)
 {
-    if constexpr (MODE == kStore) {
+    if constexpr (MODE == kStore || MODE == kStoreStream) {
         return g_bar;
     } else if constexpr (MODE == kAccumulate) {
         return prev + g_bar;
@@ -88,10 +89,13 @@ __device__ __forceinline__ void load8(const float* p, float (&x)[8])
 
 typedef float float4_native __attribute__((ext_vector_type(4)));
 
-// STREAM: the data is not read again soon (the plain aggregate), so it is written with the
-// non-temporal hint and does not stay behind as dirty lines whose write-back would compete
-// with the next kernel's reads; the parameters and the velocity of the fused update are read
-// again by the next step and are stored normally.
+// STREAM: stored with the non-temporal hint.  Used for a plain aggregate small enough to stay
+// in the memory-side cache: written normally it stays behind as dirty lines, and their
+// write-back then competes with the next kernel's reads (12 us on the statistics launch that
+// follows a 45 MB output).  The hint has a price -- the two 16-byte halves of a lane's 32 bytes
+// leave L2 as separate partial writes, and a write-bound launch with a large output runs up to
+// 1.8x slower with it -- so large outputs, which are evicted while the kernel runs anyway, and
+// the buffers of the fused update, which the next step reads again, are stored normally.
 template <bool STREAM>
 __device__ __forceinline__ void store8(float* p, const float (&x)[8])
 {
@@ -112,7 +116,7 @@ __device__ __forceinline__ void finish_group(float* o, uint64_t e0, float (&acc)
 {
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = finish<MODE>(acc[j], prev[j], vel[j], up);
-    store8<(MODE == kStore || MODE == kAccumulate)>(o, acc);
+    store8<MODE == kStoreStream>(o, acc);
     if constexpr (MODE == kSgdMomentum) store8<false>(up.velocity + e0, vel);
 }
 
@@ -129,7 +133,7 @@ __device__ __forceinline__ void finish_ragged(float* o, uint64_t e0, const float
 #pragma unroll
         for (int k = 1; k < 8; ++k) v = (j == k) ? acc[k] : v;
         float prev = 0.0f, vel = 0.0f;
-        if constexpr (MODE != kStore) prev = o[j];
+        if constexpr (MODE != kStore && MODE != kStoreStream) prev = o[j];
         if constexpr (MODE == kSgdMomentum) vel = up.velocity[e0 + j];
         o[j] = finish<MODE>(v, prev, vel, up);
         if constexpr (MODE == kSgdMomentum) up.velocity[e0 + j] = vel;
@@ -202,7 +206,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) { prev[t][j] = 0.0f; vel[t][j] = 0.0f; }
         if (e0[t] + kGroup <= bend) {
-            if constexpr (MODE != kStore) load8(out + e0[t], prev[t]);
+            if constexpr (MODE != kStore && MODE != kStoreStream) load8(out + e0[t], prev[t]);
             if constexpr (MODE == kSgdMomentum) load8(up.velocity + e0[t], vel[t]);
         }
     }
@@ -297,7 +301,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
 #pragma unroll
     for (int j = 0; j < 8; ++j) { acc[j] = 0.0f; prev[j] = 0.0f; vel[j] = 0.0f; }
     if (whole) {
-        if constexpr (MODE != kStore) load8(out + e0, prev);
+        if constexpr (MODE != kStore && MODE != kStoreStream) load8(out + e0, prev);
         if constexpr (MODE == kSgdMomentum) load8(up.velocity + e0, vel);
     }
     for (int i = 0; i < N; ++i) {
@@ -408,8 +412,11 @@ hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const
     g.tpb = (g.be + tq::kTile - 1) / tq::kTile;                        // tiles per bucket
     g.pbytes = tq_payload_bytes(d, bits);
     const tq::Update up{eta, momentum, weight_decay, velocity};
+    // outputs up to 64 MiB are streamed past the caches (see store8)
+    if (mode == tq::kStore && d * sizeof(float) <= (64ull << 20)) mode = tq::kStoreStream;
     switch (mode) {
         case tq::kStore: return launch_mode<tq::kStore>(g, out, up, st);
+        case tq::kStoreStream: return launch_mode<tq::kStoreStream>(g, out, up, st);
         case tq::kAccumulate: return launch_mode<tq::kAccumulate>(g, out, up, st);
         case tq::kSgd: return launch_mode<tq::kSgd>(g, out, up, st);
         case tq::kSgdMomentum: return launch_mode<tq::kSgdMomentum>(g, out, up, st);
