@@ -82,10 +82,28 @@ __device__ __forceinline__ void load_bits(const void* g, uint64_t e0, uint32_t (
     }
 }
 
+// The scalar fields of a bucket's record from its combined integer sums:
+// ln(a / g_min) = ln2 * (exponent + log2 mantissa) - ln g_min.
+__device__ __forceinline__ void write_scalars(tq_stats_t* S, const StatsExtra& x, uint64_t n, float g_min)
+{
+    double sum_log = 0.0;
+    if (x.n_tail)
+        sum_log = 0.6931471805599453 * ((double)x.exp_sum + (double)x.log2m_fix * 3.725290298461914e-09) -
+                  (double)x.n_tail * log((double)g_min);
+    S->n_nonfinite = x.n_nonfinite;
+    S->absmax = __uint_as_float(x.absmax_bits);            // non-negative floats order as integers
+    S->n = n;
+    S->g_min = g_min > 0.0f ? g_min : 0.0f;
+    S->reserved = 0u;
+    S->n_tail = x.n_tail;
+    S->sum_log_tail = sum_log;
+}
+
 template <int DTYPE, bool TAIL>
 __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     const PtrTable g_tab, uint64_t d, uint64_t bucket_elems, uint32_t slices, uint64_t slice_elems,
-    float g_min, char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes)
+    float g_min, char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes,
+    const MutPtrTable stats_tab)
 {
     // blockIdx.y = tensor of the batch; each tensor has its own region of the workspace
     const void* __restrict__ g = g_tab.p[blockIdx.y];
@@ -221,8 +239,11 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     __syncthreads();
 
     // partial counts of this slice, every bin (the workspace is not pre-cleared), one
-    // contiguous row per workgroup
-    uint32_t* row = ws_hist + ((uint64_t)bucket * slices + slice) * TQ_NBINS;
+    // contiguous row per workgroup; a bucket that is one slice writes its record directly and
+    // no second kernel follows
+    const bool final_record = slices == 1u;
+    tq_stats_t* S = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]) + bucket;
+    uint32_t* row = final_record ? S->hist : ws_hist + ((uint64_t)bucket * slices + slice) * TQ_NBINS;
     for (int b = threadIdx.x; b < TQ_NBINS; b += kStatsBlock) {
         uint32_t total = 0u;
 #pragma unroll
@@ -249,7 +270,8 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
             x.log2m_fix += red_u64[2][w];
         }
         x.exp_sum -= 127ll * (long long)x.n_tail;                      // biased -> unbiased exponents
-        ws_extra[(uint64_t)bucket * slices + slice] = x;
+        if (final_record) write_scalars(S, x, bend - bstart, g_min);
+        else ws_extra[(uint64_t)bucket * slices + slice] = x;
     }
 }
 
@@ -302,21 +324,11 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
         n_tail = wave_reduce_add(n_tail);
         exp_sum = wave_reduce_add(exp_sum);
         log2m_fix = wave_reduce_add(log2m_fix);
-        // ln(a / g_min) = ln2 * (exponent + log2 mantissa) - ln g_min, from exact integer sums
-        double sum_log = 0.0;
-        if (n_tail)
-            sum_log = 0.6931471805599453 * ((double)exp_sum + (double)log2m_fix * 3.725290298461914e-09) -
-                      (double)n_tail * log((double)g_min);
         if (lane == 0) {
             const uint64_t lo = (uint64_t)bucket * bucket_elems;
             const uint64_t hi = lo + bucket_elems < d ? lo + bucket_elems : d;
-            S->n_nonfinite = nonfinite;
-            S->absmax = __uint_as_float(amax);         // non-negative floats order as integers
-            S->n = hi - lo;
-            S->g_min = g_min > 0.0f ? g_min : 0.0f;
-            S->reserved = 0u;
-            S->n_tail = n_tail;
-            S->sum_log_tail = sum_log;
+            const StatsExtra x{amax, nonfinite, n_tail, exp_sum, log2m_fix};
+            write_scalars(S, x, hi - lo, g_min);
         }
     }
 }
@@ -399,7 +411,7 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
     const dim3 pgrid((unsigned)nblocks, (unsigned)count);
 #define TQ_LAUNCH_PARTIAL(DT, TL)                                                                             \
     hipLaunchKernelGGL((tq::tq_stats_partial_kernel<DT, TL>), pgrid, dim3(tq::kStatsBlock), 0, st, gt, d, p.be,   \
-                       p.slices, p.slice_elems, g_min, ws, tensor_bytes, hist_bytes)
+                       p.slices, p.slice_elems, g_min, ws, tensor_bytes, hist_bytes, stt)
     if (dtype == TQ_F32) {
         if (g_min > 0.0f) TQ_LAUNCH_PARTIAL(TQ_F32, true); else TQ_LAUNCH_PARTIAL(TQ_F32, false);
     } else {
@@ -407,7 +419,7 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
     }
 #undef TQ_LAUNCH_PARTIAL
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
+    if (err != hipSuccess || p.slices == 1) return err;           // one slice per bucket: records are written
     // one workgroup per 64 bins, plus one per bucket for the scalar fields
     const uint32_t gpb = (TQ_NBINS + tq::kReduceBins - 1) / tq::kReduceBins + 1;
     const uint64_t rblocks = p.nb * gpb;
