@@ -142,8 +142,9 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     uint64_t payload_bytes)
 {
     constexpr int T = kCompressTiles;
-    const uint32_t bucket = blockIdx.x / groups_per_bucket;
-    const uint32_t grp = blockIdx.x - bucket * groups_per_bucket;
+    const uint32_t blk = linear_block();
+    const uint32_t bucket = blk / groups_per_bucket;
+    const uint32_t grp = blk - bucket * groups_per_bucket;
     const uint64_t bstart = (uint64_t)bucket * bucket_elems;
     const uint64_t bend = bstart + bucket_elems < d_pad ? bstart + bucket_elems : d_pad;
     const uint64_t gbase = bstart + (uint64_t)grp * T * kTile;
@@ -240,7 +241,7 @@ __global__ __launch_bounds__(kBlock) void tq_simulate_kernel(
     float* __restrict__ out)
 {
     constexpr uint32_t S = (1u << BITS) - 1u;
-    const TileGeom t = tile_geom(blockIdx.x, d_pad, bucket_elems, tiles_per_bucket);
+    const TileGeom t = tile_geom(linear_block(), d_pad, bucket_elems, tiles_per_bucket);
     const uint64_t bend = t.eend < d ? t.eend : d;
     if (t.ebase >= bend) return;
     const tq_params_t* P = params + t.bucket;
@@ -340,12 +341,13 @@ hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64
     const uint64_t nb = (d_pad + be - 1) / be;
     const uint64_t tpb = ((be + tq::kTile - 1) / tq::kTile + tq::kCompressTiles - 1) / tq::kCompressTiles;
     const uint64_t nblocks = nb * tpb;                                 // tpb = workgroups per bucket
-    if (nblocks == 0 || nblocks > 0x7FFFFFFFull || count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
+    dim3 blocks;
+    if (count < 1 || count > tq::kMaxBatch || !tq::fold_grid(nblocks, tq::kBlock, (unsigned)count, blocks))
+        return hipErrorInvalidValue;
     const uint64_t pbytes = tq_payload_bytes(d, bits);
     tq::PtrTable gt{}, pt{};
     tq::MutPtrTable yt{};
     for (int i = 0; i < count; ++i) { gt.p[i] = g[i]; pt.p[i] = params[i]; yt.p[i] = payload[i]; }
-    const dim3 blocks((unsigned)nblocks, (unsigned)count);
     // non-temporal loads while the batch can still be (partly) cached from the statistics pass:
     // up to twice the 256 MiB of the memory-side cache
     const bool stream = (uint64_t)count * d * (dtype == TQ_F32 ? 4u : 2u) <= (512ull << 20);
@@ -366,9 +368,10 @@ hipError_t tq_launch_simulate(const void* g, int dtype, uint64_t d, uint64_t buc
     const uint64_t nb = (d_pad + be - 1) / be;
     const uint64_t tpb = (be + tq::kTile - 1) / tq::kTile;
     const uint64_t nblocks = nb * tpb;
-    if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    dim3 blocks;
+    if (!tq::fold_grid(nblocks, tq::kBlock, 1, blocks)) return hipErrorInvalidValue;
     const uint32_t slo = (uint32_t)seed, shi = (uint32_t)(seed >> 32);
-    const dim3 blocks((unsigned)nblocks), threads(tq::kBlock);
+    const dim3 threads(tq::kBlock);
 #define TQ_LAUNCH_SIM(DT, B)                                                                                      \
     do {                                                                                                          \
         if (accumulate)                                                                                           \

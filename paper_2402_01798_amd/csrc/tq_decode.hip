@@ -174,8 +174,9 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     constexpr uint32_t CMASK = (1u << BITS) - 1u;
     __shared__ float2 pair_tab[U * PAIRS];
 
-    const uint32_t bucket = blockIdx.x / groups_per_bucket;
-    const uint32_t grp = blockIdx.x - bucket * groups_per_bucket;
+    const uint32_t blk = linear_block();
+    const uint32_t bucket = blk / groups_per_bucket;
+    const uint32_t grp = blk - bucket * groups_per_bucket;
     const uint64_t bstart = (uint64_t)bucket * bucket_elems;
     uint64_t bend = bstart + bucket_elems < d_pad ? bstart + bucket_elems : d_pad;
     bend = bend < d ? bend : d;
@@ -284,7 +285,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
     const Update up)
 {
     constexpr uint32_t MASK = (1u << BITS) - 1u;
-    const TileGeom t = tile_geom(blockIdx.x, d_pad, bucket_elems, tiles_per_bucket);
+    const TileGeom t = tile_geom(linear_block(), d_pad, bucket_elems, tiles_per_bucket);
     if (t.ebase >= t.eend) return;
 
     __shared__ float table[TQ_MAX_WORKERS * 16];
@@ -339,8 +340,8 @@ hipError_t launch_mode(const DecodeGeom& g, float* out, const tq::Update& up, hi
         constexpr int T = 2;                                           // tiles per workgroup
         const uint64_t gpb = (g.tpb + T - 1) / T;
         const uint64_t nblocks = g.nb * gpb;
-        if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-        const dim3 blocks((unsigned)nblocks);
+        dim3 blocks;
+        if (!tq::fold_grid(nblocks, tq::kBlock, 1, blocks)) return hipErrorInvalidValue;
         const int U = N <= 1 ? 1 : (N <= 2 ? 2 : (N <= 4 ? 4 : (N <= 8 ? 8 : 16)));
 #define TQ_LAUNCH_FAST(B, UU)                                                                                \
     hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, T, MODE>), blocks, threads, 0, st, g.args, N,       \
@@ -371,8 +372,8 @@ hipError_t launch_mode(const DecodeGeom& g, float* out, const tq::Update& up, hi
     }
 
     const uint64_t nblocks = g.nb * g.tpb;
-    if (nblocks == 0 || nblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    const dim3 blocks((unsigned)nblocks);
+    dim3 blocks;
+    if (!tq::fold_grid(nblocks, tq::kBlock, 1, blocks)) return hipErrorInvalidValue;
 #define TQ_LAUNCH_GENERAL(B)                                                                                 \
     hipLaunchKernelGGL((tq::tq_decode_kernel<B, MODE>), blocks, threads, 0, st, g.args, N, g.weighted,       \
                        g.scale, g.d, g.d_pad, g.be, (uint32_t)g.tpb, g.pbytes, out, up)

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "tq.h"
 
@@ -57,6 +58,30 @@ struct PtrTable {
 struct MutPtrTable {
     void* p[kMaxBatch];
 };
+
+// A launch of `nblocks` workgroups.  The dispatch packet counts work-items per dimension in 32
+// bits, so blocks * threads of one dimension must stay below 2^32: long grids are folded into
+// (x, z), grid.y being the tensor of a batch.  Workgroups past `nblocks` (the last z-row is
+// padded) find nothing to do and exit; every kernel tests for that before touching memory.
+__device__ __forceinline__ uint32_t linear_block() { return blockIdx.x + blockIdx.z * gridDim.x; }
+
+// TQ_TEST_MAX_GRID_X (environment, read once) lowers the fold point so that tests can drive the
+// folded path of every kernel with small inputs.
+inline bool fold_grid(uint64_t nblocks, unsigned threads, unsigned count, dim3& grid)
+{
+    static const uint64_t forced = [] {
+        const char* e = getenv("TQ_TEST_MAX_GRID_X");
+        return e ? strtoull(e, nullptr, 10) : 0ull;
+    }();
+    uint64_t max_x = (1ull << 31) / threads;                       // x * threads <= 2^31
+    if (forced > 0 && forced < max_x) max_x = forced;
+    if (nblocks == 0 || nblocks > 0xFFFFFFFFull) return false;
+    const uint64_t gx = nblocks < max_x ? nblocks : max_x;
+    const uint64_t gz = (nblocks + gx - 1) / gx;
+    if (gz > 65535 || gx * gz > 0xFFFFFFFFull) return false;
+    grid = dim3((unsigned)gx, count, (unsigned)gz);
+    return true;
+}
 
 // Tile geometry shared by compress and decode.  Workgroup `blk` owns elements
 // [ebase, ebase + kTile) of bucket `bucket`, cut at `eend` (the bucket's end, the last

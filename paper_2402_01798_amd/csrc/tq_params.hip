@@ -141,12 +141,14 @@ struct DensityView {
     }
 };
 
-__global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_tab, int bits, int grid,
+__global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_tab, uint32_t nb, int bits, int grid,
                                                            float alpha_override, const MutPtrTable params_tab)
 {
     __shared__ ParamsLds L;
-    // blockIdx.x = bucket, blockIdx.y = tensor of the batch
-    const tq_stats_t* S = static_cast<const tq_stats_t*>(stats_tab.p[blockIdx.y]) + blockIdx.x;
+    // one workgroup per bucket, blockIdx.y = tensor of the batch
+    const uint32_t bucket = linear_block();
+    if (bucket >= nb) return;
+    const tq_stats_t* S = static_cast<const tq_stats_t*>(stats_tab.p[blockIdx.y]) + bucket;
     tq_params_t* params = static_cast<tq_params_t*>(params_tab.p[blockIdx.y]);
     const int tid = threadIdx.x;
     const int i0 = tid * kBinsPerLane;
@@ -326,7 +328,7 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_
         }
     }
 
-    tq_params_t* P = params + blockIdx.x;
+    tq_params_t* P = params + bucket;
     const float alpha_f = (float)(alpha > kAlphaFloor ? alpha : kAlphaFloor);
     const double af = (double)alpha_f;
     const double half = D.half_int(af);
@@ -402,11 +404,13 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_
 hipError_t tq_launch_params(const tq_stats_t* const* stats, int count, uint64_t nb, int bits, int grid,
                             float alpha_override, tq_params_t* const* params, hipStream_t st)
 {
-    if (nb == 0 || nb > 0x7FFFFFFFull || count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
+    dim3 blocks;
+    if (count < 1 || count > tq::kMaxBatch || !tq::fold_grid(nb, tq::kBlock, (unsigned)count, blocks))
+        return hipErrorInvalidValue;
     tq::PtrTable stt{};
     tq::MutPtrTable pt{};
     for (int i = 0; i < count; ++i) { stt.p[i] = stats[i]; pt.p[i] = params[i]; }
-    hipLaunchKernelGGL(tq::tq_params_kernel, dim3((unsigned)nb, (unsigned)count), dim3(tq::kBlock), 0, st, stt, bits,
+    hipLaunchKernelGGL(tq::tq_params_kernel, blocks, dim3(tq::kBlock), 0, st, stt, (uint32_t)nb, bits,
                        grid, alpha_override, pt);
     return hipGetLastError();
 }

@@ -110,14 +110,16 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
     uint32_t* __restrict__ ws_hist = reinterpret_cast<uint32_t*>(my_ws);
     StatsExtra* __restrict__ ws_extra = reinterpret_cast<StatsExtra*>(my_ws + ws_hist_bytes);
+    const uint32_t blk = linear_block();
+    if ((uint64_t)(blk / slices) * bucket_elems >= d) return;          // padding of a folded grid
     __shared__ uint32_t hist[kStatsReplicas * kStatsStride];
     __shared__ uint32_t red_u32[2][kStatsBlock / 64];
     __shared__ unsigned long long red_u64[3][kStatsBlock / 64];
     for (int i = threadIdx.x; i < kStatsReplicas * kStatsStride; i += kStatsBlock) hist[i] = 0u;
     __syncthreads();
 
-    const uint32_t bucket = blockIdx.x / slices;
-    const uint32_t slice = blockIdx.x - bucket * slices;
+    const uint32_t bucket = blk / slices;
+    const uint32_t slice = blk - bucket * slices;
     const uint64_t bstart = (uint64_t)bucket * bucket_elems;
     const uint64_t bend = bstart + bucket_elems < d ? bstart + bucket_elems : d;
     uint64_t cstart = bstart + (uint64_t)slice * slice_elems;
@@ -284,8 +286,10 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
     const uint32_t* __restrict__ ws_hist = reinterpret_cast<const uint32_t*>(my_ws);
     const StatsExtra* __restrict__ ws_extra = reinterpret_cast<const StatsExtra*>(my_ws + ws_hist_bytes);
     tq_stats_t* __restrict__ stats = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]);
-    const uint32_t bucket = blockIdx.x / groups_per_bucket;
-    const uint32_t grp = blockIdx.x - bucket * groups_per_bucket;
+    const uint32_t blk = linear_block();
+    const uint32_t bucket = blk / groups_per_bucket;
+    const uint32_t grp = blk - bucket * groups_per_bucket;
+    if ((uint64_t)bucket * bucket_elems >= d) return;                  // padding of a folded grid
     tq_stats_t* S = stats + bucket;
 
     if (grp + 1 < groups_per_bucket) {
@@ -401,14 +405,15 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
 {
     const StatsPlan p = plan_stats(d, bucket_elems, count);
     const uint64_t nblocks = p.nb * p.slices;
-    if (nblocks == 0 || nblocks > 0x7FFFFFFFull || count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
+    dim3 pgrid;
+    if (count < 1 || count > tq::kMaxBatch || !tq::fold_grid(nblocks, tq::kStatsBlock, (unsigned)count, pgrid))
+        return hipErrorInvalidValue;
     const uint64_t hist_bytes = (tq::stats_ws_hist_words(p.nb, p.slices) * 4 + 15) / 16 * 16;
     const uint64_t tensor_bytes = tq_stats_workspace_bytes_impl(d, bucket_elems);
     tq::PtrTable gt{};
     tq::MutPtrTable stt{};
     for (int i = 0; i < count; ++i) { gt.p[i] = g[i]; stt.p[i] = stats[i]; }
     char* ws = static_cast<char*>(workspace);
-    const dim3 pgrid((unsigned)nblocks, (unsigned)count);
 #define TQ_LAUNCH_PARTIAL(DT, TL)                                                                             \
     hipLaunchKernelGGL((tq::tq_stats_partial_kernel<DT, TL>), pgrid, dim3(tq::kStatsBlock), 0, st, gt, d, p.be,   \
                        p.slices, p.slice_elems, g_min, ws, tensor_bytes, hist_bytes, stt)
@@ -423,8 +428,9 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
     // one workgroup per 64 bins, plus one per bucket for the scalar fields
     const uint32_t gpb = (TQ_NBINS + tq::kReduceBins - 1) / tq::kReduceBins + 1;
     const uint64_t rblocks = p.nb * gpb;
-    if (rblocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(tq::tq_stats_reduce_kernel, dim3((unsigned)rblocks, (unsigned)count), dim3(tq::kReduceBlock), 0,
+    dim3 rgrid;
+    if (!tq::fold_grid(rblocks, tq::kReduceBlock, (unsigned)count, rgrid)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(tq::tq_stats_reduce_kernel, rgrid, dim3(tq::kReduceBlock), 0,
                        st, ws, tensor_bytes, hist_bytes, p.slices, gpb, d, p.be, g_min, stt);
     return hipGetLastError();
 }

@@ -159,3 +159,83 @@ def test_large_configs_sampled(name):
     want_out = acc * np.float32(1.0 / N)
     got_out = out[idx_dev].cpu().numpy()
     assert (got_out == want_out).all()
+
+
+def test_more_than_2_to_the_32_elements():
+    """Element indices, byte offsets and tile counts beyond 32 bits: a bf16 tensor of
+    2^32 + 6149 elements (five buckets of 2^30, the last one short and ragged), two workers.
+    Codes and averages on sampled elements around every boundary, the short bucket's
+    statistics in full, the others' by their totals."""
+    wl = synth.WORKLOADS["cfg5"]
+    d, be, bits, grid, N = (1 << 32) + 3 * 2048 + 5, 1 << 30, 2, B.GRID_NONUNIFORM, 2
+    gs_dev = [synth.make_gradient(wl, i, "cuda", d) for i in range(N)]
+    print("generated", flush=True)
+    stats = [B.alloc_stats(d, be) for _ in range(N)]
+    ws = B.alloc_stats_workspace(d, be)
+    params = [B.alloc_params(d, be) for _ in range(N)]
+    pays = [B.alloc_payload(d, bits) for _ in range(N)]
+    out = torch.empty(d, dtype=torch.float32, device="cuda")
+    for i in range(N):
+        B.tq_stats(gs_dev[i], stats[i], ws, be, 1e-6)
+        B.tq_params(stats[i], params[i], bits, grid)
+        B.tq_compress(gs_dev[i], params[i], pays[i], bits, 4242, i, 7, be)
+    B.tq_decompress_aggregate(pays, params, out, bits, be)
+    torch.cuda.synchronize()
+    print("device path done", flush=True)
+    S0 = B.stats_to_numpy(stats[0]).view(O.STATS_DTYPE)
+    assert S0["n"].tolist() == [1 << 30] * 4 + [d - (4 << 30)]
+    assert (S0["hist"].sum(axis=1) + S0["n_nonfinite"] == S0["n"]).all()
+    tail = synth.as_numpy(gs_dev[0][4 << 30:])
+    S_tail = O.stats(tail, g_min=1e-6)
+    assert (S0["hist"][4] == S_tail["hist"][0]).all() and S0["absmax"][4] == S_tail["absmax"][0]
+    assert S0["n_tail"][4] == S_tail["n_tail"][0]
+    rng = np.random.default_rng(9)
+    marks = np.array([1 << 30, 1 << 31, 3 << 30, 1 << 32, d], dtype=np.int64)
+    idx = np.unique(np.concatenate([rng.integers(0, d, size=1500), np.arange(0, 16),
+                                    (marks[:, None] + np.arange(-12, 12)[None, :]).ravel()]))
+    idx = idx[(idx >= 0) & (idx < d)]
+    idx_dev = torch.from_numpy(idx).cuda()
+    levels = np.zeros((N, idx.size), dtype=np.float32)
+    for i in range(N):
+        P_all = B.params_to_numpy(params[i]).view(O.PARAMS_DTYPE)
+        x = gs_dev[i][idx_dev].float().cpu().numpy()
+        byte_lo = (idx * bits) >> 3
+        pay_bytes = pays[i][torch.from_numpy(byte_lo).cuda()].cpu().numpy().astype(np.uint32)
+        got = (pay_bytes >> ((idx * bits) & 7).astype(np.uint32)) & 3           # 2-bit codes never straddle a byte
+        for t, e in enumerate(idx):
+            P = P_all[int(e) // be: int(e) // be + 1]
+            want = O.quantize_one(float(x[t]), P, O.rand16(4242, i, 7, int(e)))
+            assert got[t] == want, (i, int(e))
+            levels[i, t] = P["level"][0][want]
+    want_out = (levels[0] + levels[1]) * np.float32(0.5)
+    assert (out[idx_dev].cpu().numpy() == want_out).all()
+
+
+def test_group_counter_beyond_32_bits():
+    """Past 2^35 elements the group index that keys the random draws needs its high word, and
+    with buckets of 2^30 + 128 elements a tile straddles that point, so some of its lanes are
+    before the carry and some after.  Codes on sampled elements around it (compress only: a
+    bf16 tensor of 2^35 + 10000 elements is 69 GB)."""
+    wl = synth.WORKLOADS["cfg5"]
+    d, be, bits = (1 << 35) + 10_000, (1 << 30) + 128, 2
+    g = synth.make_gradient(wl, 0, "cuda", d)
+    print("generated", flush=True)
+    nb = B.num_buckets(d, be)
+    from test_oracle_quantizer import make_params, NONUNIFORM_3
+    P_all = np.concatenate([make_params(np.array(NONUNIFORM_3) * (1 + b % 3), O.GRID_NONUNIFORM) for b in range(nb)])
+    pay = B.alloc_payload(d, bits)
+    B.tq_compress(g, B.params_from_numpy(P_all), pay, bits, 0xFEEDFACE, 3, 11, be)
+    torch.cuda.synchronize()
+    print("compressed", flush=True)
+    rng = np.random.default_rng(3)
+    marks = np.array([1 << 32, 1 << 35, 31 * be, 32 * be, d], dtype=np.int64)
+    idx = np.unique(np.concatenate([rng.integers(0, d, size=1500), (1 << 35) + np.arange(-160, 2200, 7),
+                                    (marks[:, None] + np.arange(-12, 12)[None, :]).ravel()]))
+    idx = idx[(idx >= 0) & (idx < d)]
+    x = g[torch.from_numpy(idx).cuda()].float().cpu().numpy()
+    byte_lo = (idx * bits) >> 3
+    pay_bytes = pay[torch.from_numpy(byte_lo).cuda()].cpu().numpy().astype(np.uint32)
+    got = (pay_bytes >> ((idx * bits) & 7).astype(np.uint32)) & 3
+    for t, e in enumerate(idx):
+        P = P_all[int(e) // be: int(e) // be + 1]
+        assert got[t] == O.quantize_one(float(x[t]), P, O.rand16(0xFEEDFACE, 3, 11, int(e))), int(e)
