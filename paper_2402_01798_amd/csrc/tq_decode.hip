@@ -23,7 +23,21 @@ struct DecodeArgs {
     float weight[TQ_MAX_WORKERS];
 };
 
-// The 8 codes of group q (b bytes at byte q*b), little-endian in the low 8b bits.
+// The dword that holds the 8 codes of group q (b bytes at byte q*b): from bit 0, or -- b = 3,
+// the very last group of a payload, which has no fourth byte after it -- from bit 8 of the
+// dword that ends with its third byte.  The caller shifts; nothing here depends on the loaded
+// value, so the load stays in flight until the codes are used.
+template <int BITS>
+__device__ __forceinline__ uint32_t load_codes_raw(const uint8_t* p, bool room_for_dword)
+{
+    if constexpr (BITS == 4) return *reinterpret_cast<const uint32_t*>(p);
+    if constexpr (BITS == 2) return *reinterpret_cast<const uint16_t*>(p);
+    uint32_t w;
+    __builtin_memcpy(&w, room_for_dword ? p : p - 1, 4);
+    return w;
+}
+
+// The 8 codes of group q, little-endian in the low 8b bits.
 template <int BITS>
 __device__ __forceinline__ uint32_t load_codes(const uint8_t* p, bool room_for_dword)
 {
@@ -120,23 +134,22 @@ __device__ __forceinline__ void finish_group(float* o, uint64_t e0, float (&acc)
     if constexpr (MODE == kSgdMomentum) store8<false>(up.velocity + e0, vel);
 }
 
-// The ragged end of the tensor, element by element.  A rolled loop on purpose: unrolled, its
-// last store was merged into the vector stores of the whole groups, which then wrote
-// 16 + 12 + 4 bytes per lane and lost a third of the bandwidth.
+// The ragged end of the tensor, element by element (only in the last workgroup of the tensor;
+// the workgroups whose lanes all own whole groups take a separate, straight-line path, so
+// that whatever the compiler makes of these predicated stores does not touch theirs).
 template <int MODE>
 __device__ __forceinline__ void finish_ragged(float* o, uint64_t e0, const float (&acc)[8], int n_valid,
                                               const Update& up)
 {
-#pragma clang loop unroll(disable)
-    for (int j = 0; j < n_valid; ++j) {
-        float v = acc[0];
 #pragma unroll
-        for (int k = 1; k < 8; ++k) v = (j == k) ? acc[k] : v;
-        float prev = 0.0f, vel = 0.0f;
-        if constexpr (MODE != kStore && MODE != kStoreStream) prev = o[j];
-        if constexpr (MODE == kSgdMomentum) vel = up.velocity[e0 + j];
-        o[j] = finish<MODE>(v, prev, vel, up);
-        if constexpr (MODE == kSgdMomentum) up.velocity[e0 + j] = vel;
+    for (int j = 0; j < 7; ++j) {                          // a ragged group has at most 7 elements
+        if (j < n_valid) {
+            float prev = 0.0f, vel = 0.0f;
+            if constexpr (MODE != kStore && MODE != kStoreStream) prev = o[j];
+            if constexpr (MODE == kSgdMomentum) vel = up.velocity[e0 + j];
+            o[j] = finish<MODE>(acc[j], prev, vel, up);
+            if constexpr (MODE == kSgdMomentum) up.velocity[e0 + j] = vel;
+        }
     }
 }
 
@@ -197,7 +210,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     for (int u = 0; u < U; ++u) {
         const uint8_t* stream = args.payload[u < N ? u : 0];
 #pragma unroll
-        for (int t = 0; t < T; ++t) w[t][u] = load_codes<BITS>(stream + off[t], room[t]);
+        for (int t = 0; t < T; ++t) w[t][u] = load_codes_raw<BITS>(stream + off[t], room[t]);
     }
     // what the epilogue reads back (the old output, the parameters, the velocity) is requested
     // now as well, for the lanes that own a whole group
@@ -243,13 +256,14 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     const float post = weighted ? 1.0f : scale;                // x * 1.0f is exact
 
     auto lookup = [&](int t, float (&acc)[8]) {
+        const uint32_t first_bit = (BITS == 3 && !room[t]) ? 8u : 0u;   // see load_codes_raw
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                const float2 v = pair_tab[u * PAIRS + ((w[t][u] >> (2 * BITS * m)) & PMASK)];
+                const float2 v = pair_tab[u * PAIRS + ((w[t][u] >> (2 * BITS * m + first_bit)) & PMASK)];
                 acc[2 * m] = acc[2 * m] + v.x;
                 acc[2 * m + 1] = acc[2 * m + 1] + v.y;
             }
@@ -267,13 +281,13 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
             finish_group<MODE>(out + e0[t], e0[t], acc, prev[t], vel[t], up);
         }
     } else {
-        float acc[T][8];
-#pragma unroll
-        for (int t = 0; t < T; ++t) lookup(t, acc[t]);
+        // the last workgroup of a bucket: tile by tile (one tile's values live at a time)
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            if (e0[t] + kGroup <= bend) finish_group<MODE>(out + e0[t], e0[t], acc[t], prev[t], vel[t], up);
-            else if (e0[t] < bend) finish_ragged<MODE>(out + e0[t], e0[t], acc[t], (int)(bend - e0[t]), up);
+            float acc[8];
+            lookup(t, acc);
+            if (e0[t] + kGroup <= bend) finish_group<MODE>(out + e0[t], e0[t], acc, prev[t], vel[t], up);
+            else if (e0[t] < bend) finish_ragged<MODE>(out + e0[t], e0[t], acc, (int)(bend - e0[t]), up);
         }
     }
 }
