@@ -2,13 +2,13 @@
 """Benchmark of the truncated-quantization hot path on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic gradients of a
-BASELINE.json configuration (default: config 2, 11.2 M fp32 elements x 8 workers, uniform
+benchmark configuration (default: config 2, 11.2 M fp32 elements x 8 workers, uniform
 grid): for each simulated worker tq_stats -> tq_params -> tq_compress, then one fused
 tq_decompress_aggregate over the N payloads.  Inputs are resident in HBM before timing.
 
 Prints ONE JSON line.  `value` is GB/s of gradient input over the whole step (all four
 entry points); `compress_decode_gbps` is the same input over the compress + decode kernels
-only, the narrower quantity the benchmark's metric names.  `roofline` is for the dominant
+only, the narrower quantity the headline metric names.  `roofline` is for the dominant
 kernel (tq_compress_kernel), its duration measured with HIP events on the launch stream;
 `cpu_baseline` is the scalar oracle timed on this host on the same inputs.
 """
@@ -202,7 +202,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives); --gpus %d is not supported. "
-              "Each GPU would be one worker; see DESIGN.md section 5 for how the path shards." % a.gpus,
+              "Each GPU would be one worker, the aggregation one all-to-all of the packed codes." % a.gpus,
               file=sys.stderr)
         sys.exit(2)
     import torch
@@ -289,7 +289,7 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl.dtype == torch.float32 else "bf16->f32",
-        "data": "synthetic (seeded symmetric power-law gradients, see DESIGN.md section 4)",
+        "data": "synthetic (seeded symmetric power-law gradients; recipe in paper_2402_01798_amd/synth.py)",
         "config": {"workload": "%s: d=%d x N=%d workers, %s, b=%d, %s grid, bucket_elems=%d" % (
                        wl.name, wl.d, wl.workers, "fp32" if wl.dtype == torch.float32 else "bf16", bits,
                        "uniform" if grid == 0 else "non-uniform", wl.bucket_elems),

@@ -1,5 +1,6 @@
-// tq_decompress_aggregate: Alg. 1 server step of arXiv 2402.01798,
-//   out[e] = sum_i w_i * L_i[code_i(e)],
+// tq_decompress_aggregate and tq_decompress_aggregate_update: Alg. 1 server steps of
+// arXiv 2402.01798,
+//   g_bar[e] = sum_i w_i * L_i[code_i(e)],   then out = g_bar or theta <- theta - eta * g_bar,
 // for all N workers in one pass.  Each lane owns 8 consecutive output elements: it reads the
 // b bytes that hold their codes from every worker's stream, looks the levels up in LDS, adds
 // them in worker order and writes 32 contiguous bytes of fp32 once.

@@ -24,7 +24,7 @@ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
 // uniform over the wavefront (key, worker, step, high counter word) stay in SGPRs and
 // their multiplies run on the scalar unit; only the lane's counter word c0 is per-lane.
 // The xors of the first three rounds are grouped so that the uniform pair is combined on
-// the scalar unit (round 1: c1, c2, c3 uniform; round 2: c0, c1; round 3: c3); from then
+// the scalar unit (first round: c1, c2, c3 uniform; second: c0, c1; third: c3); from then
 // on every word differs per lane and each output word is one three-input xor.
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t (&out)[4])

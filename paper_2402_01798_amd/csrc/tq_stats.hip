@@ -4,7 +4,8 @@
 // caller-fixed g_min, the two terms of the tail-index estimator of Sec. V,
 //   gamma = 1 + n_tail / sum_j ln(|g_j| / g_min).
 //
-// Two launches, no atomics on global memory (same-address atomics from many workgroups
+// Two launches (one when every bucket is a single slice: the first kernel then writes the
+// records itself), no atomics on global memory (same-address atomics from many workgroups
 // serialise at about 0.14 us each on this part):
 //   1. tq_stats_partial_kernel: each workgroup reads one contiguous slice of one bucket
 //      once, histograms it into replicated LDS histograms (heavy-tailed data puts most lanes

@@ -1,5 +1,5 @@
 """The whole path on the GPU (stats -> params -> compress x N -> decode) against the oracle,
-on scaled-down and on full-size workloads of the benchmark spec."""
+on scaled-down and on full-size benchmark workloads (synth.WORKLOADS)."""
 import numpy as np
 import pytest
 import torch
@@ -92,7 +92,7 @@ def test_whole_path_with_the_biscaled_codebook(name, d, bits):
 
 
 def test_cfg2_full_size_full_arrays():
-    """BASELINE config 2 at its full size (11.2 M x 8 workers, uniform 2- and 4-bit), in the
+    """Config 2 at its full size (11.2 M x 8 workers, uniform 2- and 4-bit), in the
     launch configuration the benchmark times; every byte and every average is compared."""
     wl = synth.WORKLOADS["cfg2"]
     gs_dev = [synth.make_gradient(wl, i, "cuda") for i in range(wl.workers)]
@@ -115,7 +115,7 @@ def test_cfg2_full_size_full_arrays():
 
 @pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
 def test_large_configs_sampled(name):
-    """BASELINE configs 3-5 at full size: statistics compared in full where the oracle is
+    """Configs 3-5 at full size: statistics compared in full where the oracle is
     quick, codes and averages on sampled elements computed by the oracle one at a time."""
     wl = synth.WORKLOADS[name]
     N = wl.workers if name != "cfg3" else 4            # 4 of the 16 workers keep the run short
