@@ -101,6 +101,27 @@ def test_nothing_is_written_past_the_payload(bits, d):
     assert (got[:nbytes] == O.compress(g_np, P, 77, 0, 0)).all()
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("grid", [B.GRID_UNIFORM, B.GRID_NONUNIFORM])
+def test_extreme_magnitudes_and_subnormal_reciprocals(bits, grid):
+    """alpha = max|g| near the top of binary32 makes the reciprocal cell width subnormal (b < 4), and
+    subnormal inputs sit next to it: both sides must keep subnormals (no flush to zero)."""
+    d = 4099
+    rng = np.random.default_rng(bits * 2 + grid)
+    g_np = np.clip(rng.standard_normal(d) * 1e38, -3e38, 3e38).astype(np.float32)
+    g_np[::7] = (rng.standard_normal(g_np[::7].size) * 1e-41).astype(np.float32)     # subnormal
+    g_np[5] = np.float32(3.0e38)
+    P = oracle_params(g_np, bits, grid, alpha_override=-1.0)
+    assert float(P["inv_w"][0, 0]) < 3e-38           # subnormal at b = 2, 3; barely normal at b = 4
+    got = device_compress(torch.from_numpy(g_np).cuda(), P, bits, seed=3, worker=0, step=0).cpu().numpy()
+    assert (got == O.compress(g_np, P, 3, 0, 0)).all()
+    # and the other end: everything subnormal, alpha at its floor
+    tiny = (rng.standard_normal(d) * 1e-42).astype(np.float32)
+    P = oracle_params(tiny, bits, grid)
+    got = device_compress(torch.from_numpy(tiny).cuda(), P, bits, seed=3, worker=0, step=0).cpu().numpy()
+    assert (got == O.compress(tiny, P, 3, 0, 0)).all()
+
+
 def test_determinism_same_call_twice():
     g_dev, g_np = small_gradient("cfg2", 3, 200_000)
     P = oracle_params(g_np, 4, B.GRID_UNIFORM)
