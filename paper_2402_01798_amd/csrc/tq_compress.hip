@@ -54,6 +54,7 @@ __device__ __forceinline__ float load_one(const void* g, uint64_t e)
 // non-uniform path: entry k = (l_k, inv_w[k]).
 struct LevelLds {
     float2 e[16];
+    float search[16];      // l_j for j < s, +inf from j = s on: the table the cell search walks
 };
 
 // NaN -> +0 for a lane's 8 values.  NaN is rare, so the test is made as cheap as it can be:
@@ -85,9 +86,19 @@ __device__ __forceinline__ uint32_t quantize(float x, float rf, float alpha, flo
         const uint32_t code = (uint32_t)v;
         return code > S ? S : code;
     } else {
-        uint32_t k = 0;                                        // cell: l_k <= xc < l_{k+1}
+        // cell: l_k <= xc < l_{k+1}, i.e. k = #{j in 1..s-1 : xc >= l_j} (levels ascending)
+        uint32_t k = 0;
+        if constexpr (BITS == 2) {
 #pragma unroll
-        for (uint32_t j = 1; j < S; ++j) k += (xc >= lv[j]) ? 1u : 0u;
+            for (uint32_t j = 1; j < S; ++j) k += (xc >= lv[j]) ? 1u : 0u;
+        } else {
+            // binary search over the table padded with +inf to 2^b entries: the first step
+            // against a scalar level, the others against levels read from LDS
+            constexpr uint32_t HALF = 1u << (BITS - 1);
+            k = (xc >= lv[HALF]) ? HALF : 0u;
+#pragma unroll
+            for (uint32_t h = HALF >> 1; h >= 1; h >>= 1) k = (xc >= tab.search[k + h]) ? k + h : k;
+        }
         const float2 cell = tab.e[k];
         const float rnd = fmaf(rf, 1.0f / 65536.0f, 1.0f / 131072.0f);   // exact
         const float v = fmaf(xc - cell.x, cell.y, rnd);        // p_r of Eq. (2) + dither
@@ -161,7 +172,11 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     const float inv_step = P->inv_w[0];
     const bool nonuniform = P->grid != TQ_GRID_UNIFORM;        // uniform over the workgroup
     if (nonuniform) {
-        if (threadIdx.x < 16) tab.e[threadIdx.x] = make_float2(P->level[threadIdx.x], P->inv_w[threadIdx.x]);
+        if (threadIdx.x < 16) {
+            const float l = P->level[threadIdx.x];
+            tab.e[threadIdx.x] = make_float2(l, P->inv_w[threadIdx.x]);
+            tab.search[threadIdx.x] = threadIdx.x < ((1u << BITS) - 1u) ? l : __builtin_inff();
+        }
 #pragma unroll
         for (int j = 0; j < 16; ++j) lv[j] = P->level[j];       // wave-uniform: scalar loads
         __syncthreads();
@@ -251,7 +266,11 @@ __global__ __launch_bounds__(kBlock) void tq_simulate_kernel(
     const float alpha = P->alpha;
     const float inv_step = P->inv_w[0];
     const bool nonuniform = P->grid != TQ_GRID_UNIFORM;        // uniform over the workgroup
-    if (threadIdx.x < 16) tab.e[threadIdx.x] = make_float2(P->level[threadIdx.x], P->inv_w[threadIdx.x]);
+    if (threadIdx.x < 16) {
+        const float l = P->level[threadIdx.x];
+        tab.e[threadIdx.x] = make_float2(l, P->inv_w[threadIdx.x]);
+        tab.search[threadIdx.x] = threadIdx.x < S ? l : __builtin_inff();
+    }
 #pragma unroll
     for (int j = 0; j < 16; ++j) lv[j] = P->level[j];           // wave-uniform: scalar loads
     __syncthreads();
