@@ -89,8 +89,8 @@ __device__ __forceinline__ uint32_t quantize(float x, float rf, float alpha, flo
         // cell: l_k <= xc < l_{k+1}, i.e. k = #{j in 1..s-1 : xc >= l_j} (levels ascending)
         uint32_t k = 0;
         if constexpr (BITS == 2) {
-#pragma unroll
-            for (uint32_t j = 1; j < S; ++j) k += (xc >= lv[j]) ? 1u : 0u;
+            k = (xc >= lv[1]) ? 1u : 0u;                       // ascending levels: two selects, no adds
+            k = (xc >= lv[2]) ? 2u : k;
         } else {
             // binary search over the table padded with +inf to 2^b entries: the first step
             // against a scalar level, the others against levels read from LDS
