@@ -35,6 +35,11 @@ Readings where the paper is silent (each also listed in the design document):
   beyond max|g| is clamped there ("no truncation"), below g_min to g_min.
 * density -> codebook: level l_k is where the integral of lambda_s from -alpha
   reaches k (so that int lambda_s = s, Sec. III-A), mirrored about zero.
+
+Parity unpinned by the paper: the iteration count and tolerance, the choice of
+g_min and the candidate set of the BiScaled search are readings; the tests pin
+the fixed points and minima they lead to (closed forms, brute force), not the
+number of steps taken.
 * BiScaled: k is searched over k = 0 and the histogram's bin edges below alpha
   (beta = k alpha is then an edge), the smallest k winning a tie; the boxed
   equation is iterated like the other two with Q = min_k Q_B(alpha, k), k* re-chosen

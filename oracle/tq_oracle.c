@@ -37,6 +37,12 @@
  *     multiple of 16 bytes.
  *   - a value lying exactly on a level belongs to the cell above it
  *     (frac = 0, deterministic); NaN is encoded as +0, +-Inf as +-alpha.
+ *
+ * Parity unpinned by the paper: the bit order of the payload, the assignment
+ * of generator words to elements, the histogram's bin edges and the momentum
+ * recursion of the fused update are this build's own definitions; the tests
+ * pin them against independent readers (numpy.unpackbits, numpy.histogram,
+ * hand-computed dyadic values), not against anything the paper prints.
  */
 #include <math.h>
 #include <stddef.h>
