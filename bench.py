@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--bits", type=int, default=0, help="0 = the workload's first b")
     ap.add_argument("--grid", type=int, default=-1, help="-1 = the workload's first grid")
