@@ -53,6 +53,10 @@ def lib():
         L.tqo_truncate.restype = C.c_float
         L.tqo_quantize_one.argtypes = [C.c_float, C.c_void_p, C.c_uint32]
         L.tqo_quantize_one.restype = C.c_uint32
+        L.tqo_quantize_eq2.argtypes = [C.c_float, C.c_void_p, C.c_uint32]
+        L.tqo_quantize_eq2.restype = C.c_uint32
+        L.tqo_enumerate_draws.argtypes = [C.c_float, C.c_void_p, C.c_int, C.c_void_p]
+        L.tqo_enumerate_draws.restype = None
         L.tqo_bin.argtypes = [C.c_float]
         L.tqo_bin.restype = C.c_uint32
         L.tqo_num_buckets.argtypes = [C.c_uint64, C.c_uint64]
@@ -61,9 +65,18 @@ def lib():
         L.tqo_payload_bytes.restype = C.c_uint64
         L.tqo_stats.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_uint64,
                                 C.c_float, C.c_void_p]
+        L.tqo_stats_buckets.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_uint64,
+                                        C.c_float, C.c_void_p, C.c_uint64, C.c_uint64]
         L.tqo_compress.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_uint64,
                                    C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32,
                                    C.c_void_p]
+        L.tqo_compress_range.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_uint64,
+                                         C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32,
+                                         C.c_void_p, C.c_uint64, C.c_uint64]
+        L.tqo_decompress_aggregate_range.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p,
+                                                     C.c_int, C.c_uint64, C.c_uint64,
+                                                     C.c_int, C.c_int, C.c_void_p,
+                                                     C.c_uint64, C.c_uint64]
         L.tqo_decompress_aggregate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p,
                                                C.c_int, C.c_uint64, C.c_uint64,
                                                C.c_int, C.c_int, C.c_void_p]
@@ -120,6 +133,34 @@ def quantize_one(g, params, r):
     return int(lib().tqo_quantize_one(float(g), _ptr(p), int(r)))
 
 
+def quantize_eq2(g, params, r):
+    """Eq. (2) step by step (cell by comparison, p_r, the draw): the definition."""
+    p = np.ascontiguousarray(params).reshape(-1)[:1]
+    return int(lib().tqo_quantize_eq2(float(g), _ptr(p), int(r)))
+
+
+def enumerate_draws(g, params, eq2=False):
+    """count[c] = how many of the 65,536 draws give code c for the value ``g``."""
+    p = np.ascontiguousarray(params).reshape(-1)[:1]
+    out = np.zeros(16, dtype=np.uint32)
+    lib().tqo_enumerate_draws(float(g), _ptr(p), int(bool(eq2)), _ptr(out))
+    return out
+
+
+def _run_ranges(n_items, threads, align, call):
+    """``call(lo, hi)`` over [0, n_items) cut into ``threads`` ranges whose starts are
+    multiples of ``align``; on host threads when threads > 1 (ctypes drops the GIL)."""
+    threads = max(1, int(threads))
+    if threads == 1 or n_items <= align:
+        return [call(0, n_items)]
+    per = -(-n_items // threads)
+    per = -(-per // align) * align
+    cuts = [(lo, min(lo + per, n_items)) for lo in range(0, n_items, per)]
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        return list(ex.map(lambda c: call(*c), cuts))
+
+
 def bin_index(a):
     return int(lib().tqo_bin(float(a)))
 
@@ -132,28 +173,36 @@ def payload_bytes(d, bits):
     return int(lib().tqo_payload_bytes(d, bits))
 
 
-def stats(g, bucket_elems=0, g_min=0.0):
+def stats(g, bucket_elems=0, g_min=0.0, threads=1):
+    """Per-bucket statistics; ``threads`` > 1 spreads the buckets over host threads."""
     g = np.ascontiguousarray(g)
-    out = np.zeros(num_buckets(g.size, bucket_elems), dtype=STATS_DTYPE)
-    _check(lib().tqo_stats(_ptr(g), _dtype_code(g), g.size, bucket_elems,
-                           float(g_min), _ptr(out)), "tqo_stats")
+    nb = num_buckets(g.size, bucket_elems)
+    out = np.zeros(nb, dtype=STATS_DTYPE)
+    L, code = lib(), _dtype_code(g)
+    rcs = _run_ranges(nb, threads, 1, lambda lo, hi: L.tqo_stats_buckets(
+        _ptr(g), code, g.size, bucket_elems, float(g_min), _ptr(out), lo, hi))
+    for rc in rcs:
+        _check(rc, "tqo_stats")
     return out
 
 
-def compress(g, params, seed, worker, step, bucket_elems=0):
+def compress(g, params, seed, worker, step, bucket_elems=0, threads=1):
+    """One worker's payload; ``threads`` > 1 encodes disjoint element ranges on host threads."""
     g = np.ascontiguousarray(g)
     params = np.ascontiguousarray(params, dtype=PARAMS_DTYPE).reshape(-1)
     assert params.size == num_buckets(g.size, bucket_elems)
     bits = int(params["bits"][0])
     out = np.zeros(payload_bytes(g.size, bits), dtype=np.uint8)
-    _check(lib().tqo_compress(_ptr(g), _dtype_code(g), g.size, bucket_elems,
-                              _ptr(params), seed, worker, step, _ptr(out)),
-           "tqo_compress")
+    L, code = lib(), _dtype_code(g)
+    rcs = _run_ranges(g.size, threads, 4096, lambda lo, hi: L.tqo_compress_range(
+        _ptr(g), code, g.size, bucket_elems, _ptr(params), seed, worker, step, _ptr(out), lo, hi))
+    for rc in rcs:
+        _check(rc, "tqo_compress")
     return out
 
 
 def decompress_aggregate(payloads, params, d, bits, bucket_elems=0, weights=None,
-                         out=None):
+                         out=None, threads=1):
     """``payloads``/``params``: one array per worker.  ``out`` given => accumulate into it."""
     N = len(payloads)
     payloads = [np.ascontiguousarray(p, dtype=np.uint8) for p in payloads]
@@ -164,9 +213,12 @@ def decompress_aggregate(payloads, params, d, bits, bucket_elems=0, weights=None
     accumulate = out is not None
     if out is None:
         out = np.zeros(d, dtype=np.float32)
-    _check(lib().tqo_decompress_aggregate(pp, qq, None if w is None else _ptr(w),
-                                          N, d, bucket_elems, bits, int(accumulate),
-                                          _ptr(out)), "tqo_decompress_aggregate")
+    L = lib()
+    rcs = _run_ranges(d, threads, 4096, lambda lo, hi: L.tqo_decompress_aggregate_range(
+        pp, qq, None if w is None else _ptr(w), N, d, bucket_elems, bits, int(accumulate),
+        _ptr(out), lo, hi))
+    for rc in rcs:
+        _check(rc, "tqo_decompress_aggregate")
     return out
 
 

@@ -9,8 +9,13 @@
  * Every function walks the elements one by one in the order and notation of
  * the paper (arXiv 2402.01798):
  *   tqo_truncate            Sec. III-A, Eq. (1)   alpha-truncation T_alpha
- *   tqo_quantize_one        Sec. III-A, Eq. (2)   stochastic quantizer Q on a
- *                           codebook L = {l_0..l_s}, s = 2^b - 1
+ *   tqo_quantize_eq2        Sec. III-A, Eq. (2)   stochastic quantizer Q on a
+ *                           codebook L = {l_0..l_s}, s = 2^b - 1, step by step:
+ *                           cell by comparison with the levels, p_r, the draw
+ *   tqo_quantize_one        the code the wire format specifies: Eq. (2) as above on
+ *                           every codebook but the uniform one, where the format
+ *                           states the same rounding through the position of g in
+ *                           units of cells (see below)
  *   tqo_compress            Alg. 1, client step "quantize, send"
  *   tqo_decompress_aggregate Alg. 1, server step  g_bar = sum_i w_i g_hat_i
  *   tqo_decompress_aggregate_update  ... followed by theta <- theta - eta g_bar
@@ -22,16 +27,25 @@
  * Precision: the paper fixes none.  The quantizer's decision "round up or
  * down" yields an integer code, so it is taken in the precision of the
  * kernel under test: IEEE-754 binary32, one rounding per written operation
- * (build with -ffp-contract=off; fmaf() where written is the correctly
- * rounded fused multiply-add), no division on the per-element path.
+ * (build with -ffp-contract=off), no division on the per-element path: the
+ * quotient of Eq. (2) uses the stored reciprocal of the cell's width.
  * Reductions compared by tolerance (sum of logs) run in binary64.
  *
  * What the paper leaves open and this file fixes (readings, listed in the
  * design document as well):
  *   - "with probability p_r" (Eq. 2): a 16-bit uniform integer r drawn from
  *     the counter-based generator Philox4x32-10 (Salmon, Moraes, Dror, Shaw,
- *     SC'11) gives the dither rnd = (r + 1/2) / 2^16 and the code is
- *     k + [frac + rnd >= 1], i.e. "up" with probability frac to within 2^-16.
+ *     SC'11) gives the uniform variate u = 1 - (r + 1/2) / 2^16 (exact in
+ *     binary32), and the upper end of the cell is taken iff u <= p_r: with
+ *     probability p_r to within 2^-16, a larger r never lowering the code.
+ *   - the uniform codebook (Sec. IV-A, l_k = -alpha + k 2alpha/s): there
+ *     Eq. (2) is stochastic rounding of the position t = (g + alpha) s/(2 alpha),
+ *     code = floor(t + U), U = (r + 1/2) / 2^16, and that is how the format
+ *     states it, with t + U evaluated by two fused multiply-adds (fmaf: one
+ *     rounding each).  tqo_quantize_eq2 is the definition it has to agree with:
+ *     the tests enumerate all 65,536 draws for inputs on, next to and between
+ *     the levels and require the same cell and the same number of upward
+ *     draws to within one.
  *   - "encode using b bits": codes are laid into one little-endian bit
  *     stream, element e at bits [e*b, e*b+b), padded with zero bits to a
  *     multiple of 16 bytes.
@@ -136,31 +150,56 @@ float tqo_truncate(float g, float alpha)
     return g;
 }
 
-/* Eq. (2) on codebook P->level[0..s] with the 16-bit draw r.  Returns the
- * index of the level chosen (the b-bit code). */
-uint32_t tqo_quantize_one(float g, const tqo_params_t *P, uint32_t r)
+/* Eq. (2), step by step, on the codebook P->level[0..s] with the 16-bit draw r:
+ *   the cell Delta_k = [l_k, l_{k+1}] that holds the truncated value (a value on a
+ *   level belongs to the cell above it; the last cell is closed),
+ *   p_r = (g - l_k) / |Delta_k|   (the quotient through the stored reciprocal),
+ *   the upper end l_{k+1} with probability p_r, else l_k.
+ * Returns the index of the level chosen (the b-bit code).  Valid for any codebook. */
+uint32_t tqo_quantize_eq2(float g, const tqo_params_t *P, uint32_t r)
 {
     const uint32_t s = P->s;
     float x = g;
     if (x != x) x = 0.0f;                       /* NaN carries no information */
+    const float xc = tqo_truncate(x, P->alpha); /* Eq. (1) */
+    uint32_t k = 0;                             /* l_k <= xc < l_{k+1} */
+    for (uint32_t j = 1; j < s; ++j)
+        if (xc >= P->level[j]) k = j;
+    const float dist = xc - P->level[k];        /* g - l_k */
+    const float p_r = dist * P->inv_w[k];       /* ... / |Delta_k| */
+    const float half_grain = 1.0f / 131072.0f;
+    const float u = (1.0f - half_grain) - (float)r * (1.0f / 65536.0f);  /* 1 - (r + 1/2)/2^16, exact */
+    return (u <= p_r) ? k + 1u : k;
+}
+
+/* The code the wire format specifies for element value g and draw r. */
+uint32_t tqo_quantize_one(float g, const tqo_params_t *P, uint32_t r)
+{
+    if (P->grid != TQO_GRID_UNIFORM) return tqo_quantize_eq2(g, P, r);
+    /* uniform codebook: all cells have width 2 alpha / s, and Eq. (2) is stochastic
+     * rounding of the position of g in units of cells, counted from -alpha:
+     * floor(t + U), U = (r + 1/2) / 2^16 uniform on (0, 1) */
+    const uint32_t s = P->s;
+    float x = g;
+    if (x != x) x = 0.0f;
     const float xc = tqo_truncate(x, P->alpha);
-    const float rf = (float)r;                   /* 0 .. 65535, exact */
-    uint32_t code;
-    if (P->grid == TQO_GRID_UNIFORM) {
-        /* all cells have width 2 alpha / s: position in units of cells, measured
-         * from -alpha, plus the half-grain 2^-17 of the dither; then the dither */
-        float u = fmaf(xc, P->inv_w[0], 0.5f * (float)s + 1.0f / 131072.0f);
-        float v = fmaf(rf, 1.0f / 65536.0f, u);  /* floor(v) = k + [rnd >= 1 - frac] */
-        code = (uint32_t)v;
-    } else {
-        uint32_t k = 0;                          /* cell index: l_k <= xc < l_{k+1} */
-        for (uint32_t j = 1; j < s; ++j) k += (xc >= P->level[j]) ? 1u : 0u;
-        float rnd = fmaf(rf, 1.0f / 65536.0f, 1.0f / 131072.0f);  /* (r + 1/2) / 2^16, exact */
-        float v = fmaf(xc - P->level[k], P->inv_w[k], rnd);       /* p_r of Eq. (2) + dither */
-        code = k + (v >= 1.0f ? 1u : 0u);
-    }
+    const float t_plus_half_grain = fmaf(xc, P->inv_w[0], 0.5f * (float)s + 1.0f / 131072.0f);
+    const float v = fmaf((float)r, 1.0f / 65536.0f, t_plus_half_grain);
+    uint32_t code = (uint32_t)v;                /* v >= 0: truncation is floor */
     if (code > s) code = s;
     return code;
+}
+
+/* How many of the 65,536 draws give each code, for one value g: count[c] for c = 0..s.
+ * form 0: tqo_quantize_one, form 1: tqo_quantize_eq2.  For the tests that enumerate
+ * Lemma 1 and compare the two statements of the uniform codebook. */
+void tqo_enumerate_draws(float g, const tqo_params_t *P, int form, uint32_t count[16])
+{
+    for (int c = 0; c < 16; ++c) count[c] = 0;
+    for (uint32_t r = 0; r < 65536u; ++r) {
+        uint32_t code = form ? tqo_quantize_eq2(g, P, r) : tqo_quantize_one(g, P, r);
+        count[code & 15u]++;
+    }
 }
 
 /* --------------------------------------------------------------- layout -- */
@@ -209,13 +248,14 @@ uint32_t tqo_bin(float a)
  * (Q_U(alpha) is its CDF, the integral of p^(1/3) a sum over bins); n_tail
  * and sum_log_tail are the two terms of gamma = 1 + n / sum_j ln(g_j/g_min)
  * over |g_j| > g_min (computed only when the caller supplies g_min > 0). */
-int tqo_stats(const void *g, int dtype, uint64_t d, uint64_t bucket_elems,
-              float g_min, tqo_stats_t *stats)
+int tqo_stats_buckets(const void *g, int dtype, uint64_t d, uint64_t bucket_elems,
+                      float g_min, tqo_stats_t *stats, uint64_t b_begin, uint64_t b_end)
 {
     if (check_layout(d, bucket_elems) || (dtype != TQO_F32 && dtype != TQO_BF16))
         return TQO_EINVAL;
     const uint64_t nb = tqo_num_buckets(d, bucket_elems);
-    for (uint64_t b = 0; b < nb; ++b) {
+    if (b_begin > b_end || b_end > nb) return TQO_EINVAL;
+    for (uint64_t b = b_begin; b < b_end; ++b) {
         tqo_stats_t *S = &stats[b];
         memset(S, 0, sizeof *S);
         const uint64_t lo = b * bucket_elems;
@@ -238,21 +278,33 @@ int tqo_stats(const void *g, int dtype, uint64_t d, uint64_t bucket_elems,
     return TQO_OK;
 }
 
+/* All buckets; tqo_stats_buckets does the buckets [b_begin, b_end) only (disjoint
+ * ranges may run on different host threads). */
+int tqo_stats(const void *g, int dtype, uint64_t d, uint64_t bucket_elems,
+              float g_min, tqo_stats_t *stats)
+{
+    return tqo_stats_buckets(g, dtype, d, bucket_elems, g_min, stats, 0,
+                             tqo_num_buckets(d, bucket_elems));
+}
+
 /* ------------------------------------------------------------- compress -- */
 
 /* Alg. 1, client side: g_hat = Q[T_alpha(g)] element by element, each code
  * written into the b-bit little-endian stream.  params[bucket] holds alpha
- * and the codebook of the bucket the element lies in. */
-int tqo_compress(const void *g, int dtype, uint64_t d, uint64_t bucket_elems,
-                 const tqo_params_t *params, uint64_t seed, uint32_t worker,
-                 uint32_t step, uint8_t *payload)
+ * and the codebook of the bucket the element lies in.
+ * tqo_compress_range encodes the elements [e_begin, e_end) only, into a payload the
+ * caller has cleared; e_begin is a multiple of 8 (8 codes are whole bytes), so that
+ * disjoint ranges touch disjoint bytes and may be encoded by different host threads. */
+int tqo_compress_range(const void *g, int dtype, uint64_t d, uint64_t bucket_elems,
+                       const tqo_params_t *params, uint64_t seed, uint32_t worker,
+                       uint32_t step, uint8_t *payload, uint64_t e_begin, uint64_t e_end)
 {
     if (check_layout(d, bucket_elems) || (dtype != TQO_F32 && dtype != TQO_BF16))
         return TQO_EINVAL;
     const uint32_t bits = params[0].bits;
     if (bits < 2 || bits > 4) return TQO_EINVAL;
-    memset(payload, 0, tqo_payload_bytes(d, (int)bits));
-    for (uint64_t e = 0; e < d; ++e) {
+    if (e_begin % 8 != 0 || e_begin > e_end || e_end > d) return TQO_EINVAL;
+    for (uint64_t e = e_begin; e < e_end; ++e) {
         const tqo_params_t *P = &params[bucket_of(e, bucket_elems)];
         if (P->bits != bits || P->s != (1u << bits) - 1u) return TQO_EINVAL;
         uint32_t r = tqo_rand16(seed, worker, step, e);
@@ -262,6 +314,17 @@ int tqo_compress(const void *g, int dtype, uint64_t d, uint64_t bucket_elems,
             if ((code >> t) & 1u) payload[bitpos >> 3] |= (uint8_t)(1u << (bitpos & 7));
     }
     return TQO_OK;
+}
+
+int tqo_compress(const void *g, int dtype, uint64_t d, uint64_t bucket_elems,
+                 const tqo_params_t *params, uint64_t seed, uint32_t worker,
+                 uint32_t step, uint8_t *payload)
+{
+    if (check_layout(d, bucket_elems)) return TQO_EINVAL;
+    const uint32_t bits = params[0].bits;
+    if (bits < 2 || bits > 4) return TQO_EINVAL;
+    memset(payload, 0, tqo_payload_bytes(d, (int)bits));
+    return tqo_compress_range(g, dtype, d, bucket_elems, params, seed, worker, step, payload, 0, d);
 }
 
 static uint32_t read_code(const uint8_t *payload, uint64_t e, uint32_t bits)
@@ -300,21 +363,33 @@ static int aggregate_one(const uint8_t *const *payload,
     return TQO_OK;
 }
 
-int tqo_decompress_aggregate(const uint8_t *const *payload,
-                             const tqo_params_t *const *params,
-                             const float *weights, int N, uint64_t d,
-                             uint64_t bucket_elems, int bits, int accumulate,
-                             float *out)
+/* Elements [e_begin, e_end) only (disjoint ranges may run on different host threads). */
+int tqo_decompress_aggregate_range(const uint8_t *const *payload,
+                                   const tqo_params_t *const *params,
+                                   const float *weights, int N, uint64_t d,
+                                   uint64_t bucket_elems, int bits, int accumulate,
+                                   float *out, uint64_t e_begin, uint64_t e_end)
 {
     if (check_layout(d, bucket_elems) || N < 1 || bits < 2 || bits > 4)
         return TQO_EINVAL;
-    for (uint64_t e = 0; e < d; ++e) {
+    if (e_begin > e_end || e_end > d) return TQO_EINVAL;
+    for (uint64_t e = e_begin; e < e_end; ++e) {
         float acc;
         if (aggregate_one(payload, params, weights, N, e, bucket_elems, bits, &acc))
             return TQO_EINVAL;
         out[e] = accumulate ? out[e] + acc : acc;
     }
     return TQO_OK;
+}
+
+int tqo_decompress_aggregate(const uint8_t *const *payload,
+                             const tqo_params_t *const *params,
+                             const float *weights, int N, uint64_t d,
+                             uint64_t bucket_elems, int bits, int accumulate,
+                             float *out)
+{
+    return tqo_decompress_aggregate_range(payload, params, weights, N, d, bucket_elems, bits,
+                                          accumulate, out, 0, d);
 }
 
 /* Alg. 1, the two server steps together: g_bar = sum_i w_i g_hat_i as above,
