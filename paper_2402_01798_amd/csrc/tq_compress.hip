@@ -72,7 +72,9 @@ __device__ __forceinline__ void replace_nan(float (&x)[8])
 }
 
 // Eq. (1) then Eq. (2) for one element; `rf` is the element's 16-bit draw as a float.
-// The dither is rnd = (rf + 1/2) / 2^16 and the code is k + [frac + rnd >= 1].
+// Any codebook: cell k by comparison with the levels, p_r = (xc - l_k) * inv_w[k] (two
+// roundings), the upper end iff u = 1 - (rf + 1/2) / 2^16 <= p_r.  The uniform codebook: the
+// same rounding stated through the position in units of cells, floor(t + U), U = (rf + 1/2) / 2^16.
 template <int BITS, int GRID>
 __device__ __forceinline__ uint32_t quantize(float x, float rf, float alpha, float inv_step,
                                              const float (&lv)[16], const LevelLds& tab)
@@ -100,9 +102,9 @@ __device__ __forceinline__ uint32_t quantize(float x, float rf, float alpha, flo
             for (uint32_t h = HALF >> 1; h >= 1; h >>= 1) k = (xc >= tab.search[k + h]) ? k + h : k;
         }
         const float2 cell = tab.e[k];
-        const float rnd = fmaf(rf, 1.0f / 65536.0f, 1.0f / 131072.0f);   // exact
-        const float v = fmaf(xc - cell.x, cell.y, rnd);        // p_r of Eq. (2) + dither
-        return k + (v >= 1.0f ? 1u : 0u);
+        const float p_r = (xc - cell.x) * cell.y;              // (g - l_k) / |Delta_k| of Eq. (2)
+        const float u = fmaf(rf, -1.0f / 65536.0f, 1.0f - 1.0f / 131072.0f);   // exact
+        return k + (u <= p_r ? 1u : 0u);
     }
 }
 
