@@ -99,6 +99,26 @@ int tq_stats(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
              uint64_t workspace_bytes, void* stream);
 
 /*
+ * tq_stats_static -- tq_stats for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the partial
+ * histograms go to a scratch array of TQ_STATS_STATIC_SCRATCH_BYTES bytes that the library
+ * itself holds on every device it runs on, in place of the caller's workspace.  The call
+ * allocates and frees nothing.  Arguments and result as tq_stats; g_dev and stats_dev are
+ * still the caller's.
+ *   - TQ_EUNSUPPORTED when tq_stats_workspace_bytes(d, bucket_elems) exceeds the scratch
+ *     array (more than about 1100 buckets)
+ *   - every call on a device shares that device's array: calls that may overlap in time
+ *     on one device (different streams, no ordering between them) race and give wrong
+ *     statistics; order them, or use tq_stats with separate workspaces.  Nothing has to
+ *     be cleared between calls: every row that is read has been written by the same call.
+ *   - the device of the call is the current device (hipSetDevice); the first call on a
+ *     device looks the array's address up
+ */
+#define TQ_STATS_STATIC_SCRATCH_BYTES (4u << 20)
+int tq_stats_static(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
+                    float g_min, tq_stats_t* stats_dev, void* stream);
+
+/*
  * tq_params -- the two parameters of the quantizer, per bucket (Sec. IV):
  * truncation threshold alpha by the fixed point of the boxed equation of
  * Sec. IV-A (uniform grid, Q_U) or Sec. IV-B (non-uniform grid, Q_N), and the

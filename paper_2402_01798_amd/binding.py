@@ -59,6 +59,7 @@ def lib():
         L.tq_stats_workspace_bytes.argtypes = [u64, u64]
         L.tq_stats_workspace_bytes.restype = u64
         L.tq_stats.argtypes = [vp, i32, u64, u64, f32, vp, vp, u64, vp]
+        L.tq_stats_static.argtypes = [vp, i32, u64, u64, f32, vp, vp]
         L.tq_params.argtypes = [vp, u64, i32, i32, f32, vp, vp]
         L.tq_compress.argtypes = [vp, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
         L.tq_decompress_aggregate.argtypes = [vp, vp, vp, i32, u64, u64, i32, i32, vp, vp]
@@ -70,7 +71,7 @@ def lib():
         L.tq_stats_multi.argtypes = [vp, i32, i32, u64, u64, f32, vp, vp, u64, vp]
         L.tq_params_multi.argtypes = [vp, i32, u64, i32, i32, f32, vp, vp]
         L.tq_compress_multi.argtypes = [vp, i32, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
-        for f in (L.tq_stats, L.tq_params, L.tq_compress, L.tq_decompress_aggregate,
+        for f in (L.tq_stats, L.tq_stats_static, L.tq_params, L.tq_compress, L.tq_decompress_aggregate,
                   L.tq_decompress_aggregate_update, L.tq_stats_multi, L.tq_params_multi, L.tq_compress_multi):
             f.restype = i32
         _lib = L
@@ -136,6 +137,12 @@ def tq_stats(g, stats, workspace, bucket_elems=0, g_min=0.0):
     _check(lib().tq_stats(_dev(g, "g"), _dtype_code(g), g.numel(), bucket_elems, g_min,
                           _dev(stats, "stats"), _dev(workspace, "workspace"), workspace.numel(),
                           _stream()), "tq_stats")
+    return stats
+
+
+def tq_stats_static(g, stats, bucket_elems=0, g_min=0.0):
+    _check(lib().tq_stats_static(_dev(g, "g"), _dtype_code(g), g.numel(), bucket_elems, g_min,
+                                 _dev(stats, "stats"), _stream()), "tq_stats_static")
     return stats
 
 

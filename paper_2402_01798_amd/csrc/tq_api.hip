@@ -7,6 +7,7 @@
 hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
                            float g_min, tq_stats_t* const* stats, void* workspace, hipStream_t st);
 uint64_t tq_stats_workspace_bytes_impl(uint64_t d, uint64_t bucket_elems);
+hipError_t tq_stats_static_scratch(void** out);
 hipError_t tq_launch_params(const tq_stats_t* const* stats, int count, uint64_t nb, int bits, int grid,
                             float alpha_override, tq_params_t* const* params, hipStream_t st);
 hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
@@ -89,6 +90,19 @@ int tq_stats(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems, fl
 {
     return tq_stats_multi(&g_dev, 1, dtype, d, bucket_elems, g_min, &stats_dev, workspace_dev, workspace_bytes,
                           stream);
+}
+
+int tq_stats_static(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems, float g_min,
+                    tq_stats_t* stats_dev, void* stream)
+{
+    int rc;
+    if ((rc = check_layout(d, bucket_elems)) || (rc = check_dtype(dtype))) return rc;
+    if (tq_stats_workspace_bytes_impl(d, bucket_elems) > TQ_STATS_STATIC_SCRATCH_BYTES) return TQ_EUNSUPPORTED;
+    void* ws = nullptr;
+    if (tq_stats_static_scratch(&ws) != hipSuccess) return TQ_EHIP;
+    // the remaining checks, and the launch, are tq_stats's own
+    return tq_stats_multi(&g_dev, 1, dtype, d, bucket_elems, g_min, &stats_dev, ws,
+                          TQ_STATS_STATIC_SCRATCH_BYTES, stream);
 }
 
 int tq_params_multi(const tq_stats_t* const* stats_host, int count, uint64_t nb, int bits, int grid,

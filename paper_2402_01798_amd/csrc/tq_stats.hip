@@ -17,7 +17,16 @@
 //      counts and the log-sum.
 // Counts are integers and the tail's log-sum travels as exact integer sums, so the result
 // depends neither on scheduling nor on how the tensor was sliced or batched.
+#include <atomic>
+
 #include "tq_device.h"
+
+// Scratch of tq_stats_static: the partial histograms of the workgroups, held by the library in
+// place of the caller's workspace, for callers that cannot allocate.  Every device the library
+// runs on holds its own copy of the array until the process ends.  Host code never passes
+// this name to a kernel or a copy: it is a host-side stand-in, and the device address comes
+// from hipGetSymbolAddress (tq_stats_static_scratch below).
+static __device__ __align__(256) unsigned char scratch[TQ_STATS_STATIC_SCRATCH_BYTES];
 
 namespace tq {
 
@@ -396,6 +405,27 @@ uint64_t tq_stats_workspace_bytes_impl(uint64_t d, uint64_t bucket_elems)
     const uint64_t hist_bytes = tq::stats_ws_hist_words(nb, slices) * 4;
     const uint64_t bytes = (hist_bytes + 15) / 16 * 16 + nb * slices * sizeof(tq::StatsExtra);
     return (bytes + 255) / 256 * 256;                                  // regions of a batch stay aligned
+}
+
+// Device address of this device's copy of `scratch`, looked up once per device with that
+// device current and kept for the life of the process.  Devices beyond the table are refused.
+hipError_t tq_stats_static_scratch(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> known[kMaxDevices];
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* ptr = known[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!ptr) return hipErrorInvalidSymbol;
+        known[dev].store(ptr, std::memory_order_release);          // every thread finds the same address
+    }
+    *out = ptr;
+    return hipSuccess;
 }
 
 // Host side of tq_stats / tq_stats_multi after the argument checks of the C entry points:

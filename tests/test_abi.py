@@ -26,7 +26,8 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
-    assert set(names) == {"tq_num_buckets", "tq_payload_bytes", "tq_stats", "tq_stats_workspace_bytes", "tq_params",
+    assert set(names) == {"tq_num_buckets", "tq_payload_bytes", "tq_stats", "tq_stats_workspace_bytes", "tq_stats_static",
+                          "tq_params",
                           "tq_compress", "tq_decompress_aggregate", "tq_decompress_aggregate_update",
                           "tq_quantize_dequantize", "tq_strerror",
                           "tq_stats_multi", "tq_params_multi", "tq_compress_multi"}
