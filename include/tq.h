@@ -43,7 +43,8 @@ enum { TQ_GRID_UNIFORM = 0, TQ_GRID_NONUNIFORM = 1, TQ_GRID_BISCALED = 2 };  /* 
 #define TQ_F_ALPHA_CLAMPED_MAX 1u  /* fixed point at or beyond max|g|: alpha = max|g| */
 #define TQ_F_GAMMA_CLAMPED     2u  /* tail index estimate below 2.02, lifted to it   */
 #define TQ_F_NOT_CONVERGED     4u  /* 100 iterations without meeting 1e-10           */
-#define TQ_F_DEGENERATE        8u  /* no finite non-zero data, or no usable tail      */
+#define TQ_F_DEGENERATE        8u  /* no finite non-zero data (alpha = 2^-64 unless the
+                                      caller gave one), or no usable tail (alpha = max|g|) */
 #define TQ_F_ALPHA_OVERRIDE   16u  /* alpha given by the caller                       */
 #define TQ_F_ALPHA_CLAMPED_MIN 32u /* fixed point at or below g_min, lifted           */
 

@@ -259,8 +259,11 @@ def tq_params_one(stats, bits, grid, alpha_override=0.0):
     flags = 0
     g_min = gamma = rho = 0.0
     if dens.n <= 0 or dens.absmax <= 0.0:
-        flags |= FLAG_DEGENERATE
+        flags |= FLAG_DEGENERATE                 # nothing to design from; a given threshold still holds
         alpha = ALPHA_FLOOR
+        if alpha_override > 0.0:
+            flags |= FLAG_ALPHA_OVERRIDE
+            alpha = float(alpha_override)
     else:
         g_min, n_tail, sum_log = estimate_tail(stats, dens)
         tail_ok = g_min > 0.0 and n_tail > 0 and sum_log > 0.0 and g_min < dens.absmax

@@ -11,7 +11,8 @@ import numpy as np
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libtq.so")
+# TQ_LIBRARY_PATH selects another build of the same library (the tests' grid-fold build)
+LIB_PATH = os.environ.get("TQ_LIBRARY_PATH") or os.path.join(HERE, "libtq.so")
 
 OK, EINVAL, EALIGN, EUNSUPPORTED, EHIP = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1

@@ -14,6 +14,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtq.so")
+# the same sources with the grid-fold test hook compiled in (tests/test_gpu_folded_grid.py only)
+FOLD_TEST_LIB = os.path.join(HERE, "libtq_foldtest.so")
 
 SOURCES = ["tq_api.hip", "tq_stats.hip", "tq_params.hip", "tq_compress.hip", "tq_decode.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -30,14 +32,15 @@ def _stale(out, deps):
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = False, extra_flags=(), verbose: bool = False) -> str:
+def build(force: bool = False, extra_flags=(), verbose: bool = False, lib: str = LIB, obj_dir: str = OBJ_DIR) -> str:
     """Compile every source to an object (in parallel) and link the shared library."""
-    os.makedirs(OBJ_DIR, exist_ok=True)
-    headers = [os.path.join(ROOT, "include", "tq.h"), os.path.join(CSRC, "tq_device.h"), __file__]
+    os.makedirs(obj_dir, exist_ok=True)
+    headers = [os.path.join(ROOT, "include", "tq.h"), os.path.join(CSRC, "tq_device.h"),
+               os.path.join(CSRC, "tq_layout.h"), __file__]
 
     def compile_one(src):
         s = os.path.join(CSRC, src)
-        o = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+        o = os.path.join(obj_dir, src.replace(".hip", ".o"))
         if force or _stale(o, [s] + headers):
             cmd = [HIPCC, *FLAGS, *extra_flags, "-c", s, "-o", o]
             if verbose:
@@ -47,13 +50,20 @@ def build(force: bool = False, extra_flags=(), verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    if force or _stale(LIB, objs):
-        tmp = LIB + ".tmp.%d" % os.getpid()
+    if force or _stale(lib, objs):
+        tmp = lib + ".tmp.%d" % os.getpid()
         subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp])
-        os.replace(tmp, LIB)
-    return LIB
+        os.replace(tmp, lib)
+    return lib
+
+
+def build_fold_test(force: bool = False, verbose: bool = False) -> str:
+    """The test build: -DTQ_TEST_GRID_FOLD lets TQ_TEST_MAX_GRID_X lower the point at which long
+    grids are folded, so that the folded path of every kernel can be driven with small inputs."""
+    return build(force, ("-DTQ_TEST_GRID_FOLD",), verbose, FOLD_TEST_LIB, os.path.join(OBJ_DIR, "foldtest"))
 
 
 if __name__ == "__main__":
     import sys
     print(build(force="--force" in sys.argv, verbose=True))
+    print(build_fold_test(force="--force" in sys.argv, verbose=True))

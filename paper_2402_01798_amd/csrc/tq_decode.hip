@@ -15,6 +15,7 @@
 #include <type_traits>
 
 #include "tq_device.h"
+#include "tq_layout.h"
 
 namespace tq {
 
@@ -24,33 +25,16 @@ struct DecodeArgs {
     float weight[TQ_MAX_WORKERS];
 };
 
-// The dword that holds the 8 codes of group q (b bytes at byte q*b): from bit 0, or -- b = 3,
-// the very last group of a payload, which has no fourth byte after it -- from bit 8 of the
-// dword that ends with its third byte.  The caller shifts; nothing here depends on the loaded
-// value, so the load stays in flight until the codes are used.
+// The word that holds the 8 codes of a group, as code_load (tq_layout.h) places it.  Nothing
+// here depends on the loaded value, so the load stays in flight until the codes are used; the
+// caller shifts by CodeLoad::first_bit (non-zero only for the last groups of a 3-bit payload).
 template <int BITS>
-__device__ __forceinline__ uint32_t load_codes_raw(const uint8_t* p, bool room_for_dword)
+__device__ __forceinline__ uint32_t load_code_word(const uint8_t* stream, const CodeLoad& c)
 {
-    if constexpr (BITS == 4) return *reinterpret_cast<const uint32_t*>(p);
-    if constexpr (BITS == 2) return *reinterpret_cast<const uint16_t*>(p);
+    if constexpr (BITS == 2) return *reinterpret_cast<const uint16_t*>(stream + c.load_off);
     uint32_t w;
-    __builtin_memcpy(&w, room_for_dword ? p : p - 1, 4);
+    __builtin_memcpy(&w, stream + c.load_off, 4);          // b = 3: byte-aligned only
     return w;
-}
-
-// The 8 codes of group q, little-endian in the low 8b bits.
-template <int BITS>
-__device__ __forceinline__ uint32_t load_codes(const uint8_t* p, bool room_for_dword)
-{
-    if constexpr (BITS == 4) return *reinterpret_cast<const uint32_t*>(p);
-    if constexpr (BITS == 2) return *reinterpret_cast<const uint16_t*>(p);
-    // 3 bytes at an odd offset: one unaligned dword load.  The very last group of a payload
-    // may have no fourth byte after it; it reads the dword that ends with its third byte.
-    const uint8_t* q = room_for_dword ? p : p - 1;
-    uint32_t w;
-    __builtin_memcpy(&w, q, 4);
-    w = room_for_dword ? w : w >> 8;
-    return w & 0x00FFFFFFu;
 }
 
 // What happens to the aggregate g_bar of an element (the MODE of the kernels below):
@@ -198,20 +182,19 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     if (gstart >= bend) return;
 
     // this lane's group in each tile; lanes past the end read group 0 (always present)
-    uint64_t e0[T], off[T];
-    bool room[T];
+    uint64_t e0[T];
+    CodeLoad cl[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         e0[t] = gstart + (uint64_t)t * kTile + (uint64_t)threadIdx.x * kGroup;
-        off[t] = e0[t] < bend ? (e0[t] >> 3) * (uint64_t)BITS : 0;
-        room[t] = off[t] + 4 <= payload_bytes;
+        cl[t] = code_load(e0[t] < bend ? e0[t] >> 3 : 0, BITS, payload_bytes);
     }
     uint32_t w[T][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint8_t* stream = args.payload[u < N ? u : 0];
 #pragma unroll
-        for (int t = 0; t < T; ++t) w[t][u] = load_codes_raw<BITS>(stream + off[t], room[t]);
+        for (int t = 0; t < T; ++t) w[t][u] = load_code_word<BITS>(stream, cl[t]);
     }
     // what the epilogue reads back (the old output, the parameters, the velocity) is requested
     // now as well, for the lanes that own a whole group
@@ -257,14 +240,14 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     const float post = weighted ? 1.0f : scale;                // x * 1.0f is exact
 
     auto lookup = [&](int t, float (&acc)[8]) {
-        const uint32_t first_bit = (BITS == 3 && !room[t]) ? 8u : 0u;   // see load_codes_raw
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                const float2 v = pair_tab[u * PAIRS + ((w[t][u] >> (2 * BITS * m + first_bit)) & PMASK)];
+                const uint32_t codes = BITS == 3 ? w[t][u] >> cl[t].first_bit : w[t][u];
+                const float2 v = pair_tab[u * PAIRS + ((codes >> (2 * BITS * m)) & PMASK)];
                 acc[2 * m] = acc[2 * m] + v.x;
                 acc[2 * m + 1] = acc[2 * m + 1] + v.y;
             }
@@ -309,8 +292,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
 
     const uint64_t e0 = t.ebase + (uint64_t)threadIdx.x * kGroup;
     if (e0 >= t.eend || e0 >= d) return;
-    const uint64_t byte_off = (e0 >> 3) * (uint64_t)BITS;
-    const bool room = byte_off + 4 <= payload_bytes;
+    const CodeLoad cl = code_load(e0 >> 3, BITS, payload_bytes);
 
     const bool whole = e0 + kGroup <= d;
     float acc[8], prev[8], vel[8];
@@ -321,7 +303,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
         if constexpr (MODE == kSgdMomentum) load8(up.velocity + e0, vel);
     }
     for (int i = 0; i < N; ++i) {
-        const uint32_t w = load_codes<BITS>(args.payload[i] + byte_off, room);
+        const uint32_t w = load_code_word<BITS>(args.payload[i], cl) >> cl.first_bit;
         const float* row = table + i * 16;
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = acc[j] + row[(w >> (j * BITS)) & MASK];

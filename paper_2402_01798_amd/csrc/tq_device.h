@@ -65,14 +65,19 @@ struct MutPtrTable {
 // padded) find nothing to do and exit; every kernel tests for that before touching memory.
 __device__ __forceinline__ uint32_t linear_block() { return blockIdx.x + blockIdx.z * gridDim.x; }
 
-// TQ_TEST_MAX_GRID_X (environment, read once) lowers the fold point so that tests can drive the
-// folded path of every kernel with small inputs.
+// Builds with -DTQ_TEST_GRID_FOLD (the test build only) read TQ_TEST_MAX_GRID_X from the
+// environment, once, to lower the fold point, so that tests can drive the folded path of every
+// kernel with small inputs; the product build has no such hook.
 inline bool fold_grid(uint64_t nblocks, unsigned threads, unsigned count, dim3& grid)
 {
+#ifdef TQ_TEST_GRID_FOLD
     static const uint64_t forced = [] {
         const char* e = getenv("TQ_TEST_MAX_GRID_X");
         return e ? strtoull(e, nullptr, 10) : 0ull;
     }();
+#else
+    constexpr uint64_t forced = 0;
+#endif
     uint64_t max_x = (1ull << 31) / threads;                       // x * threads <= 2^31
     if (forced > 0 && forced < max_x) max_x = forced;
     if (nblocks == 0 || nblocks > 0xFFFFFFFFull) return false;

@@ -280,8 +280,10 @@ __global__ __launch_bounds__(kBlock) void tq_params_kernel(const PtrTable stats_
     uint32_t flags = 0;
     double gamma = 0.0, rho = 0.0, alpha;
     if (n <= 0.0 || absmax <= 0.0) {
+        // nothing finite and non-zero to design from; a threshold the caller gives is still honoured
         flags |= TQ_F_DEGENERATE;
         alpha = kAlphaFloor;
+        if (alpha_override > 0.0f) { flags |= TQ_F_ALPHA_OVERRIDE; alpha = (double)alpha_override; }
         g_min = 0.0;
     } else {
         double n_tail, sum_log;

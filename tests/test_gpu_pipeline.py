@@ -92,8 +92,10 @@ def test_whole_path_with_the_biscaled_codebook(name, d, bits):
 
 
 def test_cfg2_full_size_full_arrays():
-    """Config 2 at its full size (11.2 M x 8 workers, uniform 2- and 4-bit), in the
-    launch configuration the benchmark times; every byte and every average is compared."""
+    """Config 2 at its full size (11.2 M x 8 workers, uniform 2- and 4-bit) through the
+    single-tensor entry points, one call per worker; every byte and every average is compared.
+    (tests/test_gpu_full_size.py does the same through the batched entry points the benchmark
+    times, for every configuration.)"""
     wl = synth.WORKLOADS["cfg2"]
     gs_dev = [synth.make_gradient(wl, i, "cuda") for i in range(wl.workers)]
     for bits in wl.bits:

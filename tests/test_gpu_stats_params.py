@@ -102,6 +102,13 @@ def test_params_override_and_degenerate(override):
             torch.cuda.synchronize()
             want = OP.tq_params(B.stats_to_numpy(st).view(O.STATS_DTYPE), 2, grid)
             assert_params_close(B.params_to_numpy(pr), want)
+            # a threshold the caller gives is used even when there is nothing to design from
+            B.tq_params(st, pr, 2, grid, 0.5)
+            torch.cuda.synchronize()
+            want = OP.tq_params(B.stats_to_numpy(st).view(O.STATS_DTYPE), 2, grid, 0.5)
+            got = B.params_to_numpy(pr)
+            assert float(got["alpha"][0]) == 0.5
+            assert_params_close(got, want)
 
 
 def test_cfg1_alpha_is_the_closed_form_value():

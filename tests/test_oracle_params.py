@@ -260,6 +260,10 @@ def test_degenerate_inputs_give_usable_parameters():
         P = OP.tq_params_one(zeros, 3, grid)
         assert int(P["flags"]) & OP.FLAG_DEGENERATE and float(P["alpha"]) > 0
         assert np.isfinite(P["inv_w"]).all() and (np.diff(P["level"][:8]) > 0).all()
+        # a threshold the caller gives is used even when there is nothing to design from
+        P = OP.tq_params_one(zeros, 3, grid, alpha_override=0.5)
+        assert float(P["alpha"]) == 0.5 and P["level"][0] == -0.5 and P["level"][7] == 0.5
+        assert int(P["flags"]) & OP.FLAG_DEGENERATE and int(P["flags"]) & OP.FLAG_ALPHA_OVERRIDE
     const = O.stats(np.full(256, 0.25, dtype=np.float32))[0]       # one point mass
     for grid in (O.GRID_UNIFORM, O.GRID_NONUNIFORM):
         P = OP.tq_params_one(const, 2, grid)
