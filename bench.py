@@ -110,7 +110,7 @@ class Path:
         self.B.tq_params(self.stats[i], self.params[i], self.bits, self.grid)
 
     def compress_i(self, i):
-        self.B.tq_compress(self.g[i], self.params[i], self.pay[i], self.bits, 0x5EED, i, self.step_no, self.be)
+        self.B.tq_compress(self.g[i], self.params[i], self.pay[i], self.bits, 0x5EED, i, self.step_no, self.be, self.grid)
 
     def decode(self):
         self.B.tq_decompress_aggregate(self.pay, self.params, self.out, self.bits, self.be)
@@ -122,7 +122,7 @@ class Path:
         self.B.tq_params_multi(self.stats, self.params, self.bits, self.grid)
 
     def compress_all(self):
-        self.B.tq_compress_multi(self.g, self.params, self.pay, self.bits, 0x5EED, 0, self.step_no, self.be)
+        self.B.tq_compress_multi(self.g, self.params, self.pay, self.bits, 0x5EED, 0, self.step_no, self.be, self.grid)
 
     def step(self):
         """One pass of the whole path over all N simulated workers.

@@ -151,10 +151,16 @@ int tq_params(const tq_stats_t* stats_dev, uint64_t nb, int bits, int grid,
  *   params_dev   [tq_num_buckets]; all records must carry the same bits
  *                (read on the device: a mismatch cannot be reported)
  *   bits         b in {2,3,4}, the bits of params_dev
+ *   grid         the codebook family of params_dev as it was given to tq_params (TQ_GRID_*).
+ *                It chooses the shape of the launch and nothing else: the records live on
+ *                the device, and the two families run fastest with different numbers of
+ *                tiles per workgroup.  Every bucket is encoded as ITS record says, so the
+ *                payload is the same whatever is passed here; a wrong value costs about a
+ *                tenth of the speed.
  *   payload_dev  [tq_payload_bytes(d, bits)] written in full, padding included
  */
 int tq_compress(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
-                const tq_params_t* params_dev, int bits, uint64_t seed,
+                const tq_params_t* params_dev, int bits, int grid, uint64_t seed,
                 uint32_t worker, uint32_t step, void* payload_dev, void* stream);
 
 /*
@@ -174,7 +180,7 @@ int tq_params_multi(const tq_stats_t* const* stats_host, int count, uint64_t nb,
                     void* stream);
 int tq_compress_multi(const void* const* g_host, int count, int dtype, uint64_t d,
                       uint64_t bucket_elems, const tq_params_t* const* params_host, int bits,
-                      uint64_t seed, uint32_t first_worker, uint32_t step,
+                      int grid, uint64_t seed, uint32_t first_worker, uint32_t step,
                       void* const* payload_host, void* stream);
 
 /*

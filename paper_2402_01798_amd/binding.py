@@ -62,7 +62,7 @@ def lib():
         L.tq_stats.argtypes = [vp, i32, u64, u64, f32, vp, vp, u64, vp]
         L.tq_stats_static.argtypes = [vp, i32, u64, u64, f32, vp, vp]
         L.tq_params.argtypes = [vp, u64, i32, i32, f32, vp, vp]
-        L.tq_compress.argtypes = [vp, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
+        L.tq_compress.argtypes = [vp, i32, u64, u64, vp, i32, i32, u64, u32, u32, vp, vp]
         L.tq_decompress_aggregate.argtypes = [vp, vp, vp, i32, u64, u64, i32, i32, vp, vp]
         L.tq_decompress_aggregate_update.argtypes = [vp, vp, vp, i32, u64, u64, i32, f32, f32, f32, vp, vp, vp]
         L.tq_quantize_dequantize.argtypes = [vp, i32, u64, u64, vp, i32, u64, u32, u32, i32, vp, vp]
@@ -71,7 +71,7 @@ def lib():
         L.tq_strerror.restype = C.c_char_p
         L.tq_stats_multi.argtypes = [vp, i32, i32, u64, u64, f32, vp, vp, u64, vp]
         L.tq_params_multi.argtypes = [vp, i32, u64, i32, i32, f32, vp, vp]
-        L.tq_compress_multi.argtypes = [vp, i32, i32, u64, u64, vp, i32, u64, u32, u32, vp, vp]
+        L.tq_compress_multi.argtypes = [vp, i32, i32, u64, u64, vp, i32, i32, u64, u32, u32, vp, vp]
         for f in (L.tq_stats, L.tq_stats_static, L.tq_params, L.tq_compress, L.tq_decompress_aggregate,
                   L.tq_decompress_aggregate_update, L.tq_stats_multi, L.tq_params_multi, L.tq_compress_multi):
             f.restype = i32
@@ -156,14 +156,15 @@ def tq_params(stats, params, bits, grid, alpha_override=0.0):
     return params
 
 
-def tq_compress(g, params, payload, bits, seed, worker, step, bucket_elems=0):
+def tq_compress(g, params, payload, bits, seed, worker, step, bucket_elems=0, grid=GRID_UNIFORM):
+    """``grid``: the family ``params`` was designed with; it only shapes the launch (see tq.h)."""
     d = g.numel()
     if params.numel() != num_buckets(d, bucket_elems) * PARAMS_BYTES:
         raise ValueError("params buffer does not match the number of buckets")
     if payload.numel() < payload_bytes(d, bits):
         raise ValueError("payload buffer too small")
     _check(lib().tq_compress(_dev(g, "g"), _dtype_code(g), d, bucket_elems, _dev(params, "params"),
-                             bits, seed, worker, step, _dev(payload, "payload"), _stream()),
+                             bits, grid, seed, worker, step, _dev(payload, "payload"), _stream()),
            "tq_compress")
     return payload
 
@@ -200,7 +201,7 @@ def tq_params_multi(stats, params, bits, grid, alpha_override=0.0):
     return params
 
 
-def tq_compress_multi(gs, params, payloads, bits, seed, first_worker, step, bucket_elems=0):
+def tq_compress_multi(gs, params, payloads, bits, seed, first_worker, step, bucket_elems=0, grid=GRID_UNIFORM):
     d = gs[0].numel()
     for g, q, p in zip(gs, params, payloads):
         if g.numel() != d or g.dtype != gs[0].dtype:
@@ -208,7 +209,7 @@ def tq_compress_multi(gs, params, payloads, bits, seed, first_worker, step, buck
         if q.numel() != num_buckets(d, bucket_elems) * PARAMS_BYTES or p.numel() < payload_bytes(d, bits):
             raise ValueError("params / payload buffer size does not match d")
     _check(lib().tq_compress_multi(_ptr_array(gs, "g"), len(gs), _dtype_code(gs[0]), d, bucket_elems,
-                                   _ptr_array(params, "params"), bits, seed, first_worker, step,
+                                   _ptr_array(params, "params"), bits, grid, seed, first_worker, step,
                                    _ptr_array(payloads, "payload"), _stream()), "tq_compress_multi")
     return payloads
 

@@ -11,8 +11,8 @@ hipError_t tq_stats_static_scratch(void** out);
 hipError_t tq_launch_params(const tq_stats_t* const* stats, int count, uint64_t nb, int bits, int grid,
                             float alpha_override, tq_params_t* const* params, hipStream_t st);
 hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
-                              const tq_params_t* const* params, int bits, uint64_t seed, uint32_t first_worker,
-                              uint32_t step, void* const* payload, hipStream_t st);
+                              const tq_params_t* const* params, int bits, int grid, uint64_t seed,
+                              uint32_t first_worker, uint32_t step, void* const* payload, hipStream_t st);
 hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const* params,
                             const float* weights, int N, uint64_t d, uint64_t bucket_elems, int bits,
                             int mode, float eta, float momentum, float weight_decay, float* velocity,
@@ -39,6 +39,10 @@ int check_layout(uint64_t d, uint64_t bucket_elems)
 
 int check_dtype(int dtype) { return (dtype == TQ_F32 || dtype == TQ_BF16) ? TQ_OK : TQ_EINVAL; }
 int check_bits(int bits) { return (bits >= 2 && bits <= 4) ? TQ_OK : TQ_EINVAL; }
+int check_grid(int grid)
+{
+    return (grid == TQ_GRID_UNIFORM || grid == TQ_GRID_NONUNIFORM || grid == TQ_GRID_BISCALED) ? TQ_OK : TQ_EINVAL;
+}
 int from_hip(hipError_t e) { return e == hipSuccess ? TQ_OK : (e == hipErrorInvalidValue ? TQ_EUNSUPPORTED : TQ_EHIP); }
 
 }  // namespace
@@ -110,7 +114,7 @@ int tq_params_multi(const tq_stats_t* const* stats_host, int count, uint64_t nb,
 {
     int rc;
     if ((rc = check_bits(bits))) return rc;
-    if (grid != TQ_GRID_UNIFORM && grid != TQ_GRID_NONUNIFORM && grid != TQ_GRID_BISCALED) return TQ_EINVAL;
+    if ((rc = check_grid(grid))) return rc;
     if (nb == 0 || count < 1 || !stats_host || !params_host) return TQ_EINVAL;
     if (count > TQ_MAX_WORKERS) return TQ_EUNSUPPORTED;
     if (alpha_override != alpha_override || alpha_override > 3.0e38f) return TQ_EINVAL;
@@ -129,26 +133,27 @@ int tq_params(const tq_stats_t* stats_dev, uint64_t nb, int bits, int grid, floa
 }
 
 int tq_compress_multi(const void* const* g_host, int count, int dtype, uint64_t d, uint64_t bucket_elems,
-                      const tq_params_t* const* params_host, int bits, uint64_t seed, uint32_t first_worker,
-                      uint32_t step, void* const* payload_host, void* stream)
+                      const tq_params_t* const* params_host, int bits, int grid, uint64_t seed,
+                      uint32_t first_worker, uint32_t step, void* const* payload_host, void* stream)
 {
     int rc;
     if ((rc = check_layout(d, bucket_elems)) || (rc = check_dtype(dtype)) || (rc = check_bits(bits))) return rc;
+    if ((rc = check_grid(grid))) return rc;
     if (count < 1 || !g_host || !params_host || !payload_host) return TQ_EINVAL;
     if (count > TQ_MAX_WORKERS) return TQ_EUNSUPPORTED;
     for (int i = 0; i < count; ++i) {
         if (!g_host[i] || !params_host[i] || !payload_host[i]) return TQ_EINVAL;
         if (!aligned16(g_host[i]) || !aligned16(params_host[i]) || !aligned16(payload_host[i])) return TQ_EALIGN;
     }
-    return from_hip(tq_launch_compress(g_host, count, dtype, d, bucket_elems, params_host, bits, seed,
+    return from_hip(tq_launch_compress(g_host, count, dtype, d, bucket_elems, params_host, bits, grid, seed,
                                        first_worker, step, payload_host, static_cast<hipStream_t>(stream)));
 }
 
 int tq_compress(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
-                const tq_params_t* params_dev, int bits, uint64_t seed, uint32_t worker, uint32_t step,
+                const tq_params_t* params_dev, int bits, int grid, uint64_t seed, uint32_t worker, uint32_t step,
                 void* payload_dev, void* stream)
 {
-    return tq_compress_multi(&g_dev, 1, dtype, d, bucket_elems, &params_dev, bits, seed, worker, step,
+    return tq_compress_multi(&g_dev, 1, dtype, d, bucket_elems, &params_dev, bits, grid, seed, worker, step,
                              &payload_dev, stream);
 }
 

@@ -4,11 +4,10 @@
 // One lane owns 8 consecutive elements: they share one Philox4x32-10 call (8 x 16 random
 // bits) and their codes are exactly b bytes of the payload, so a wavefront reads 2 KiB
 // (fp32) or 1 KiB (bf16) of gradient and writes 64*b contiguous bytes.
+#include <type_traits>
+
 #include "tq_device.h"
 
-#ifndef TQ_COMPRESS_TILES
-#define TQ_COMPRESS_TILES 1
-#endif
 
 namespace tq {
 
@@ -50,12 +49,21 @@ __device__ __forceinline__ float load_one(const void* g, uint64_t e)
     return __uint_as_float((uint32_t) static_cast<const uint16_t*>(g)[e] << 16);
 }
 
-// Levels and inverse widths of one bucket, kept in LDS for the per-lane lookup of the
-// non-uniform path: entry k = (l_k, inv_w[k]).
+// Levels and inverse widths of one bucket, kept in LDS for the per-lane look-ups of the
+// level-table path: entry j = (l_j, inv_w[j], pivot_j, -), 16 bytes, where pivot_j = l_j for
+// j < s and +inf from j = s on: the table the cell search walks.  The search carries the
+// BYTE offset of its current entry, so no look-up needs an index-to-address shift.
 struct LevelLds {
-    float2 e[16];
-    float search[16];      // l_j for j < s, +inf from j = s on: the table the cell search walks
+    float4 e[16];
 };
+
+__device__ __forceinline__ void fill_level_lds(LevelLds& tab, const tq_params_t* P, uint32_t s)
+{
+    if (threadIdx.x < 16) {
+        const float l = P->level[threadIdx.x];
+        tab.e[threadIdx.x] = make_float4(l, P->inv_w[threadIdx.x], threadIdx.x < s ? l : __builtin_inff(), 0.0f);
+    }
+}
 
 // NaN -> +0 for a lane's 8 values.  NaN is rare, so the test is made as cheap as it can be:
 // one unordered compare per PAIR of values, and the replacement itself only in wavefronts
@@ -72,39 +80,76 @@ __device__ __forceinline__ void replace_nan(float (&x)[8])
 }
 
 // Eq. (1) then Eq. (2) for one element; `rf` is the element's 16-bit draw as a float.
-// Any codebook: cell k by comparison with the levels, p_r = (xc - l_k) * inv_w[k] (two
+// Any codebook: cell k by comparison with the levels, p_r = (x - l_k) * inv_w[k] (two
 // roundings), the upper end iff u = 1 - (rf + 1/2) / 2^16 <= p_r.  The uniform codebook: the
 // same rounding stated through the position in units of cells, floor(t + U), U = (rf + 1/2) / 2^16.
+//
+// The truncation of Eq. (1) is written out only where it changes something.  On the level-table
+// path it changes nothing: beyond +alpha the cell is still the last one and p_r only grows past
+// 1 (or stays 0 for an empty cell), so the upper end alpha is taken for every draw, which is
+// what T_alpha(x) = alpha gives; below -alpha the cell is the first one and p_r < 0, so the
+// lower end -alpha is taken for every draw; +-Inf go the same ways (Inf times a zero reciprocal
+// is NaN, and u <= NaN is false: the lower end, as for the truncated value).  Requires what
+// tq_params_t promises: level[s] = alpha, level[0] = -alpha, finite inv_w.
+// Uniform codebook: the code of one element.
+template <int BITS>
+__device__ __forceinline__ uint32_t quantize_uniform(float x, float rf, float alpha, float inv_step)
+{
+    constexpr uint32_t S = (1u << BITS) - 1u;
+    const float xc = __builtin_amdgcn_fmed3f(x, -alpha, alpha);  // Eq. (1); the caller has replaced NaN
+    // position in units of cells from -alpha, plus the dither's half grain; then the draw
+    const float u = fmaf(xc, inv_step, 0.5f * (float)S + 1.0f / 131072.0f);
+    const float v = fmaf(rf, 1.0f / 65536.0f, u);              // floor(v) = k + [rnd >= 1 - frac]
+    const uint32_t code = (uint32_t)v;
+    return code > S ? S : code;
+}
+
+// Level-table path: 16 * k for the cell k that holds x (l_k <= x < l_{k+1}; levels ascending),
+// i.e. the byte offset of the cell's entry in LevelLds.
+template <int BITS>
+__device__ __forceinline__ uint32_t cell_offset(float x, const float (&lv)[16], const LevelLds& tab)
+{
+    uint32_t a;
+    if constexpr (BITS == 2) {
+        a = (x >= lv[1]) ? 16u : 0u;                           // two selects, no adds
+        a = (x >= lv[2]) ? 32u : a;
+    } else {
+        // binary search over the pivots (padded with +inf to 2^b entries): the first pivot is a
+        // scalar, the second a select between two scalars, the others are read from LDS at
+        // (current entry + step), the step folded into the instruction's offset field
+        constexpr uint32_t HALF = 1u << (BITS - 1), QUARTER = HALF >> 1;
+        const bool top = x >= lv[HALF];
+        const float pivot = top ? lv[HALF + QUARTER] : lv[QUARTER];
+        a = top ? 16u * HALF : 0u;
+        a |= (x >= pivot) ? 16u * QUARTER : 0u;
+        const char* base = reinterpret_cast<const char*>(tab.e);
+#pragma unroll
+        for (uint32_t h = QUARTER >> 1; h >= 1; h >>= 1) {
+            const float pv = *reinterpret_cast<const float*>(base + a + (16u * h + 8u));
+            a |= (x >= pv) ? 16u * h : 0u;
+        }
+    }
+    return a;
+}
+
+// Level-table path: does the element take the upper end of its cell?  p_r and the draw.
+__device__ __forceinline__ bool rounds_up(float x, float rf, uint32_t a, const LevelLds& tab)
+{
+    const float2 cell = *reinterpret_cast<const float2*>(reinterpret_cast<const char*>(tab.e) + a);
+    const float p_r = (x - cell.x) * cell.y;                   // (g - l_k) / |Delta_k| of Eq. (2)
+    const float u = fmaf(rf, -1.0f / 65536.0f, 1.0f - 1.0f / 131072.0f);   // 1 - (r + 1/2) / 2^16, exact
+    return u <= p_r;
+}
+
 template <int BITS, int GRID>
 __device__ __forceinline__ uint32_t quantize(float x, float rf, float alpha, float inv_step,
                                              const float (&lv)[16], const LevelLds& tab)
 {
-    constexpr uint32_t S = (1u << BITS) - 1u;
-    const float xc = __builtin_amdgcn_fmed3f(x, -alpha, alpha);  // Eq. (1); the caller has replaced NaN
     if constexpr (GRID == TQ_GRID_UNIFORM) {
-        // position in units of cells from -alpha, plus the dither's half grain; then the draw
-        const float u = fmaf(xc, inv_step, 0.5f * (float)S + 1.0f / 131072.0f);
-        const float v = fmaf(rf, 1.0f / 65536.0f, u);          // floor(v) = k + [rnd >= 1 - frac]
-        const uint32_t code = (uint32_t)v;
-        return code > S ? S : code;
+        return quantize_uniform<BITS>(x, rf, alpha, inv_step);
     } else {
-        // cell: l_k <= xc < l_{k+1}, i.e. k = #{j in 1..s-1 : xc >= l_j} (levels ascending)
-        uint32_t k = 0;
-        if constexpr (BITS == 2) {
-            k = (xc >= lv[1]) ? 1u : 0u;                       // ascending levels: two selects, no adds
-            k = (xc >= lv[2]) ? 2u : k;
-        } else {
-            // binary search over the table padded with +inf to 2^b entries: the first step
-            // against a scalar level, the others against levels read from LDS
-            constexpr uint32_t HALF = 1u << (BITS - 1);
-            k = (xc >= lv[HALF]) ? HALF : 0u;
-#pragma unroll
-            for (uint32_t h = HALF >> 1; h >= 1; h >>= 1) k = (xc >= tab.search[k + h]) ? k + h : k;
-        }
-        const float2 cell = tab.e[k];
-        const float p_r = (xc - cell.x) * cell.y;              // (g - l_k) / |Delta_k| of Eq. (2)
-        const float u = fmaf(rf, -1.0f / 65536.0f, 1.0f - 1.0f / 131072.0f);   // exact
-        return k + (u <= p_r ? 1u : 0u);
+        const uint32_t a = cell_offset<BITS>(x, lv, tab);
+        return (a >> 4) + (rounds_up(x, rf, a, tab) ? 1u : 0u);
     }
 }
 
@@ -115,15 +160,31 @@ __device__ __forceinline__ uint32_t encode_group(const float (&x)[8], const uint
                                                  float alpha, float inv_step, const float (&lv)[16],
                                                  const LevelLds& tab)
 {
-    uint32_t word = 0;
+    if constexpr (GRID == TQ_GRID_UNIFORM) {
+        uint32_t word = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t r = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
-        uint32_t code = quantize<BITS, GRID>(x[j], (float)r, alpha, inv_step, lv, tab);
-        if (PARTIAL && j >= n_valid) code = 0;
-        word |= code << (j * BITS);
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t r = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
+            uint32_t code = quantize_uniform<BITS>(x[j], (float)r, alpha, inv_step);
+            if (PARTIAL && j >= n_valid) code = 0;
+            word |= code << (j * BITS);
+        }
+        return word;
+    } else {
+        // code = k + up: the cells' offsets 16 k are merged into one word (shifted into place,
+        // four bits too high), the upward roundings into another; their sum is the packed group
+        uint32_t cells = 0, ups = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t r = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
+            uint32_t a = cell_offset<BITS>(x[j], lv, tab);
+            bool up = rounds_up(x[j], (float)r, a, tab);
+            if (PARTIAL && j >= n_valid) { a = 0; up = false; }
+            cells |= (j * BITS >= 4) ? a << (j * BITS - 4) : a >> (4 - j * BITS);
+            ups |= up ? 1u << (j * BITS) : 0u;
+        }
+        return cells + ups;
     }
-    return word;
 }
 
 // `room` = bytes of the payload from `out` on.  A payload is a multiple of 16 bytes, so a
@@ -143,24 +204,37 @@ __device__ __forceinline__ void store_codes(uint8_t* out, uint32_t word, uint64_
     }
 }
 
-// Tiles per workgroup: each lane keeps this many 32-byte (fp32) reads in flight while it
-// computes its draws.
-constexpr int kCompressTiles = TQ_COMPRESS_TILES;
+// Tiles per workgroup (256 threads, every thread one group in every tile, all reads requested
+// first).  The two codebook families want different numbers, measured on MI355X:
+//   * the uniform path costs few instructions per element and runs at the speed of its memory
+//     traffic when the running wavefronts together cover a small window of the gradient: on
+//     8 x 124 M fp32, 670 us with one tile per workgroup against 745 us with two, whether the
+//     two are requested together, one after the other, adjacent or far apart;
+//   * the level-table path costs twice the instructions, and a wavefront that holds only one
+//     group has nothing in flight while it computes: with two tiles 8 x 124 M fp32 at b = 2 take
+//     718 us instead of 785, 16 x 25.6 M at b = 3 307 instead of 346, and 4 x 10^9 bf16 with four
+//     tiles (a bf16 tile is half the bytes) 1790 instead of 2440.
+// The family is a property of the parameter records, which live on the device, so the host
+// chooses by the family the caller names (tq_compress's `grid`); the kernel itself reads every
+// bucket's record and computes what the record says, whatever shape it was launched in.
+constexpr int compress_tiles(int dtype, bool table_path)
+{
+    return dtype == TQ_F32 ? (table_path ? 2 : 1) : (table_path ? 4 : 2);
+}
 
-template <int DTYPE, int BITS, bool STREAM>
+template <int DTYPE, int BITS, bool STREAM, int T>
 __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     const PtrTable g_tab, uint64_t d, uint64_t d_pad, uint64_t bucket_elems,
     uint32_t groups_per_bucket, const PtrTable params_tab, uint32_t seed_lo,
     uint32_t seed_hi, uint32_t first_worker, uint32_t step, const MutPtrTable payload_tab,
     uint64_t payload_bytes)
 {
-    constexpr int T = kCompressTiles;
     const uint32_t blk = linear_block();
     const uint32_t bucket = blk / groups_per_bucket;
     const uint32_t grp = blk - bucket * groups_per_bucket;
     const uint64_t bstart = (uint64_t)bucket * bucket_elems;
     const uint64_t bend = bstart + bucket_elems < d_pad ? bstart + bucket_elems : d_pad;
-    const uint64_t gbase = bstart + (uint64_t)grp * T * kTile;
+    const uint64_t gbase = bstart + (uint64_t)grp * T * kTile;            // first element of the workgroup
     if (gbase >= bend) return;                                 // idle workgroup of a short last bucket
     // blockIdx.y = tensor of the batch; its worker id keys the random draws
     const void* __restrict__ g = g_tab.p[blockIdx.y];
@@ -173,12 +247,9 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     const float alpha = P->alpha;
     const float inv_step = P->inv_w[0];
     const bool nonuniform = P->grid != TQ_GRID_UNIFORM;        // uniform over the workgroup
+    const uint32_t lane = threadIdx.x;                         // this thread's group within a tile
     if (nonuniform) {
-        if (threadIdx.x < 16) {
-            const float l = P->level[threadIdx.x];
-            tab.e[threadIdx.x] = make_float2(l, P->inv_w[threadIdx.x]);
-            tab.search[threadIdx.x] = threadIdx.x < ((1u << BITS) - 1u) ? l : __builtin_inff();
-        }
+        fill_level_lds(tab, P, (1u << BITS) - 1u);
 #pragma unroll
         for (int j = 0; j < 16; ++j) lv[j] = P->level[j];       // wave-uniform: scalar loads
         __syncthreads();
@@ -189,7 +260,7 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     auto draw = [&](uint64_t ebase, uint32_t (&rw)[4]) {
         const uint64_t qb = ebase >> 3;                        // first group of the tile (uniform)
         const uint32_t qb_lo = (uint32_t)qb, qb_hi = (uint32_t)(qb >> 32);
-        const uint32_t q_lo = qb_lo + threadIdx.x;
+        const uint32_t q_lo = qb_lo + lane;
         if (qb_lo <= 0xFFFFFFFFu - kBlock) philox4x32_10(q_lo, qb_hi, worker, step, seed_lo, seed_hi, rw);
         else philox4x32_10(q_lo, qb_hi + (q_lo < qb_lo ? 1u : 0u), worker, step, seed_lo, seed_hi, rw);
     };
@@ -200,7 +271,7 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
         float x[T][8];
         uint32_t rw[T][4];
 #pragma unroll
-        for (int t = 0; t < T; ++t) load_group<DTYPE, STREAM>(g, gbase + (uint64_t)t * kTile + (uint64_t)threadIdx.x * kGroup, x[t]);
+        for (int t = 0; t < T; ++t) load_group<DTYPE, STREAM>(g, gbase + (uint64_t)t * kTile + (uint64_t)lane * kGroup, x[t]);
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             draw(gbase + (uint64_t)t * kTile, rw[t]);
@@ -212,7 +283,7 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
             const uint32_t word =
                 nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x[t], rw[t], 8, alpha, inv_step, lv, tab)
                            : encode_group<BITS, TQ_GRID_UNIFORM, false>(x[t], rw[t], 8, alpha, inv_step, lv, tab);
-            store_codes<BITS>(payload + (((gbase + (uint64_t)t * kTile) >> 3) + threadIdx.x) * (uint64_t)BITS, word);
+            store_codes<BITS>(payload + (((gbase + (uint64_t)t * kTile) >> 3) + lane) * (uint64_t)BITS, word);
         }
         return;
     }
@@ -221,8 +292,8 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     // ragged last group element by element
     for (int t = 0; t < T; ++t) {
         const uint64_t ebase = gbase + (uint64_t)t * kTile;
-        const uint64_t e0 = ebase + (uint64_t)threadIdx.x * kGroup;
-        const uint64_t byte_off = ((ebase >> 3) + threadIdx.x) * (uint64_t)BITS;
+        const uint64_t e0 = ebase + (uint64_t)lane * kGroup;
+        const uint64_t byte_off = ((ebase >> 3) + lane) * (uint64_t)BITS;
         if (e0 >= bend || byte_off >= payload_bytes) continue;
         uint32_t word = 0;                                     // groups wholly in the padding encode as 0
         if (e0 + kGroup <= d) {
@@ -268,11 +339,7 @@ __global__ __launch_bounds__(kBlock) void tq_simulate_kernel(
     const float alpha = P->alpha;
     const float inv_step = P->inv_w[0];
     const bool nonuniform = P->grid != TQ_GRID_UNIFORM;        // uniform over the workgroup
-    if (threadIdx.x < 16) {
-        const float l = P->level[threadIdx.x];
-        tab.e[threadIdx.x] = make_float2(l, P->inv_w[threadIdx.x]);
-        tab.search[threadIdx.x] = threadIdx.x < S ? l : __builtin_inff();
-    }
+    fill_level_lds(tab, P, S);
 #pragma unroll
     for (int j = 0; j < 16; ++j) lv[j] = P->level[j];           // wave-uniform: scalar loads
     __syncthreads();
@@ -325,7 +392,7 @@ __global__ __launch_bounds__(kBlock) void tq_simulate_kernel(
 
 namespace {
 
-template <int DTYPE, bool STREAM>
+template <int DTYPE, bool STREAM, int T>
 hipError_t launch(int bits, dim3 blocks, hipStream_t st, const tq::PtrTable& g, uint64_t d, uint64_t d_pad,
                   uint64_t be, uint32_t tpb, const tq::PtrTable& params, uint64_t seed, uint32_t first_worker,
                   uint32_t step, const tq::MutPtrTable& payload, uint64_t pbytes)
@@ -334,15 +401,15 @@ hipError_t launch(int bits, dim3 blocks, hipStream_t st, const tq::PtrTable& g, 
     const dim3 threads(tq::kBlock);
     switch (bits) {
         case 2:
-            hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 2, STREAM>), blocks, threads, 0, st, g, d, d_pad, be,
+            hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 2, STREAM, T>), blocks, threads, 0, st, g, d, d_pad, be,
                                tpb, params, slo, shi, first_worker, step, payload, pbytes);
             break;
         case 3:
-            hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 3, STREAM>), blocks, threads, 0, st, g, d, d_pad, be,
+            hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 3, STREAM, T>), blocks, threads, 0, st, g, d, d_pad, be,
                                tpb, params, slo, shi, first_worker, step, payload, pbytes);
             break;
         default:
-            hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 4, STREAM>), blocks, threads, 0, st, g, d, d_pad, be,
+            hipLaunchKernelGGL((tq::tq_compress_kernel<DTYPE, 4, STREAM, T>), blocks, threads, 0, st, g, d, d_pad, be,
                                tpb, params, slo, shi, first_worker, step, payload, pbytes);
             break;
     }
@@ -353,15 +420,18 @@ hipError_t launch(int bits, dim3 blocks, hipStream_t st, const tq::PtrTable& g, 
 
 // Host side of tq_compress / tq_compress_multi after the argument checks of the C entry
 // points: `count` same-shaped tensors in one launch (grid.y), workers first_worker + 0..count-1.
+// `grid` (the family the caller names) only chooses the number of tiles per workgroup.
 hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
-                              const tq_params_t* const* params, int bits, uint64_t seed, uint32_t first_worker,
-                              uint32_t step, void* const* payload, hipStream_t st)
+                              const tq_params_t* const* params, int bits, int grid, uint64_t seed,
+                              uint32_t first_worker, uint32_t step, void* const* payload, hipStream_t st)
 {
     const uint64_t d_pad = (d + 127) / 128 * 128;
     const uint64_t be = bucket_elems ? bucket_elems : d_pad;
     const uint64_t nb = (d_pad + be - 1) / be;
-    const uint64_t tpb = ((be + tq::kTile - 1) / tq::kTile + tq::kCompressTiles - 1) / tq::kCompressTiles;
-    const uint64_t nblocks = nb * tpb;                                 // tpb = workgroups per bucket
+    const bool table_path = grid != TQ_GRID_UNIFORM;
+    const uint64_t tt = (uint64_t)tq::compress_tiles(dtype, table_path);
+    const uint64_t tpb = ((be + tq::kTile - 1) / tq::kTile + tt - 1) / tt;    // workgroups per bucket
+    const uint64_t nblocks = nb * tpb;
     dim3 blocks;
     if (count < 1 || count > tq::kMaxBatch || !tq::fold_grid(nblocks, tq::kBlock, (unsigned)count, blocks))
         return hipErrorInvalidValue;
@@ -372,10 +442,13 @@ hipError_t tq_launch_compress(const void* const* g, int count, int dtype, uint64
     // non-temporal loads while the batch can still be (partly) cached from the statistics pass:
     // up to twice the 256 MiB of the memory-side cache
     const bool stream = (uint64_t)count * d * (dtype == TQ_F32 ? 4u : 2u) <= (512ull << 20);
-#define TQ_LAUNCH_COMPRESS(DT, ST) \
-    launch<DT, ST>(bits, blocks, st, gt, d, d_pad, be, (uint32_t)tpb, pt, seed, first_worker, step, yt, pbytes)
-    if (dtype == TQ_F32) return stream ? TQ_LAUNCH_COMPRESS(TQ_F32, true) : TQ_LAUNCH_COMPRESS(TQ_F32, false);
-    return stream ? TQ_LAUNCH_COMPRESS(TQ_BF16, true) : TQ_LAUNCH_COMPRESS(TQ_BF16, false);
+#define TQ_LAUNCH_COMPRESS(DT, ST, TP) \
+    launch<DT, ST, tq::compress_tiles(DT, TP)>(bits, blocks, st, gt, d, d_pad, be, (uint32_t)tpb, pt, seed, \
+                                               first_worker, step, yt, pbytes)
+#define TQ_LAUNCH_COMPRESS_ST(DT, TP) (stream ? TQ_LAUNCH_COMPRESS(DT, true, TP) : TQ_LAUNCH_COMPRESS(DT, false, TP))
+    if (dtype == TQ_F32) return table_path ? TQ_LAUNCH_COMPRESS_ST(TQ_F32, true) : TQ_LAUNCH_COMPRESS_ST(TQ_F32, false);
+    return table_path ? TQ_LAUNCH_COMPRESS_ST(TQ_BF16, true) : TQ_LAUNCH_COMPRESS_ST(TQ_BF16, false);
+#undef TQ_LAUNCH_COMPRESS_ST
 #undef TQ_LAUNCH_COMPRESS
 }
 

@@ -19,11 +19,14 @@ def oracle_params(g_np, bits, grid, bucket_elems=0, g_min=0.0, alpha_override=0.
     return OP.tq_params(O.stats(g_np, bucket_elems=bucket_elems, g_min=g_min), bits, grid, alpha_override)
 
 
-def device_compress(g_dev, params_np, bits, seed, worker, step, bucket_elems=0):
+def device_compress(g_dev, params_np, bits, seed, worker, step, bucket_elems=0, grid=None):
+    """``grid`` = the family named to tq_compress (shapes the launch only); default: the records' own."""
     params_dev = B.params_from_numpy(params_np)
     payload = B.alloc_payload(g_dev.numel(), bits)
     payload.fill_(0xA5)                       # the library must overwrite every byte, padding included
-    B.tq_compress(g_dev, params_dev, payload, bits, seed, worker, step, bucket_elems)
+    if grid is None:
+        grid = int(np.asarray(params_np["grid"]).reshape(-1)[0])
+    B.tq_compress(g_dev, params_dev, payload, bits, seed, worker, step, bucket_elems, grid)
     torch.cuda.synchronize()
     return payload
 

@@ -75,9 +75,10 @@ def test_bad_arguments_are_rejected_without_a_device(L):
     assert L.tq_params(p, 1, 3, 3, 0.0, p, None) == B.EINVAL                 # grid
     assert L.tq_params(p, 0, 3, 0, 0.0, p, None) == B.EINVAL                 # no buckets
     assert L.tq_params(p, 1, 3, 0, float("nan"), p, None) == B.EINVAL
-    assert L.tq_compress(p, 0, 1000, 0, p, 1, 0, 0, 0, p, None) == B.EINVAL  # bits
-    assert L.tq_compress(p, 0, 1000, 0, p, 3, 0, 0, 0, odd, None) == B.EALIGN
-    assert L.tq_compress(p, 0, 1 << 41, 0, p, 3, 0, 0, 0, p, None) == B.EUNSUPPORTED
+    assert L.tq_compress(p, 0, 1000, 0, p, 1, 0, 0, 0, 0, p, None) == B.EINVAL  # bits
+    assert L.tq_compress(p, 0, 1000, 0, p, 3, 7, 0, 0, 0, p, None) == B.EINVAL  # grid
+    assert L.tq_compress(p, 0, 1000, 0, p, 3, 0, 0, 0, 0, odd, None) == B.EALIGN
+    assert L.tq_compress(p, 0, 1 << 41, 0, p, 3, 1, 0, 0, 0, p, None) == B.EUNSUPPORTED
     arr = (C.c_void_p * 2)(0x1000, 0x2000)
     assert L.tq_decompress_aggregate(arr, arr, None, 0, 1000, 0, 3, 0, p, None) == B.EINVAL    # N = 0
     assert L.tq_decompress_aggregate(arr, arr, None, 65, 1000, 0, 3, 0, p, None) == B.EUNSUPPORTED

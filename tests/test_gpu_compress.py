@@ -128,3 +128,21 @@ def test_determinism_same_call_twice():
     a = device_compress(g_dev, P, 4, 11, 3, 1).cpu().numpy()
     b = device_compress(g_dev, P, 4, 11, 3, 1).cpu().numpy()
     assert (a == b).all()
+
+
+@pytest.mark.parametrize("wl,dtype_name", [("cfg4", "fp32"), ("cfg5", "bf16")])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("family", [B.GRID_UNIFORM, B.GRID_NONUNIFORM])
+def test_the_family_named_to_tq_compress_shapes_the_launch_only(wl, dtype_name, bits, family):
+    """tq_compress's `grid` picks the number of tiles per workgroup; every bucket is encoded as its
+    own record says.  So the payload must equal the oracle's whichever family is named, for
+    records of either family -- over several workgroups of either shape, a short last bucket and
+    a ragged end."""
+    bucket = 3 * 4096 + 128
+    d = 5 * bucket + 1234 + 5
+    g_dev, g_np = small_gradient(wl, 1, d)
+    P = oracle_params(g_np, bits, family, bucket_elems=bucket)
+    want = O.compress(g_np, P, 21, 2, 9, bucket_elems=bucket)
+    for named in (B.GRID_UNIFORM, B.GRID_NONUNIFORM, B.GRID_BISCALED):
+        got = device_compress(g_dev, P, bits, 21, 2, 9, bucket, grid=named).cpu().numpy()
+        assert (got == want).all(), (family, named)

@@ -36,7 +36,7 @@ def run_batched(wl, gs_dev, bits, grid, seed, step):
     out = torch.full((d,), float("nan"), dtype=torch.float32, device="cuda")
     B.tq_stats_multi(gs_dev, stats, ws, be, wl.g_min)
     B.tq_params_multi(stats, params, bits, grid)
-    B.tq_compress_multi(gs_dev, params, pays, bits, seed, 0, step, be)
+    B.tq_compress_multi(gs_dev, params, pays, bits, seed, 0, step, be, grid)
     B.tq_decompress_aggregate(pays, params, out, bits, be)
     torch.cuda.synchronize()
     return stats, params, pays, out

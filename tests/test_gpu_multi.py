@@ -24,7 +24,7 @@ def test_multi_equals_single(name, d, count):
     for i in range(count):
         B.tq_stats(gs[i], st1[i], ws1, be, wl.g_min)
         B.tq_params(st1[i], pr1[i], bits, grid)
-        B.tq_compress(gs[i], pr1[i], py1[i], bits, 99, 10 + i, 3, be)
+        B.tq_compress(gs[i], pr1[i], py1[i], bits, 99, 10 + i, 3, be, grid)
     # batched path
     wsm = torch.empty(count * B.stats_workspace_bytes(d, be), dtype=torch.uint8, device="cuda")
     stm = [B.alloc_stats(d, be).fill_(0x11) for _ in range(count)]
@@ -32,7 +32,7 @@ def test_multi_equals_single(name, d, count):
     pym = [B.alloc_payload(d, bits).fill_(0x33) for _ in range(count)]
     B.tq_stats_multi(gs, stm, wsm, be, wl.g_min)
     B.tq_params_multi(stm, prm, bits, grid)
-    B.tq_compress_multi(gs, prm, pym, bits, 99, 10, 3, be)
+    B.tq_compress_multi(gs, prm, pym, bits, 99, 10, 3, be, grid)
     torch.cuda.synchronize()
     for i in range(count):
         assert torch.equal(st1[i], stm[i]), ("stats", i)

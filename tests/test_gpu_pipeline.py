@@ -24,7 +24,7 @@ def run_device(wl, gs_dev, bits, grid, seed, step):
     for i in range(N):
         B.tq_stats(gs_dev[i], stats[i], ws, wl.bucket_elems, wl.g_min)
         B.tq_params(stats[i], params[i], bits, grid)
-        B.tq_compress(gs_dev[i], params[i], pays[i], bits, seed, i, step, wl.bucket_elems)
+        B.tq_compress(gs_dev[i], params[i], pays[i], bits, seed, i, step, wl.bucket_elems, grid)
     B.tq_decompress_aggregate(pays, params, out, bits, wl.bucket_elems)
     torch.cuda.synchronize()
     return stats, params, pays, out
@@ -180,7 +180,7 @@ def test_more_than_2_to_the_32_elements():
     for i in range(N):
         B.tq_stats(gs_dev[i], stats[i], ws, be, 1e-6)
         B.tq_params(stats[i], params[i], bits, grid)
-        B.tq_compress(gs_dev[i], params[i], pays[i], bits, 4242, i, 7, be)
+        B.tq_compress(gs_dev[i], params[i], pays[i], bits, 4242, i, 7, be, grid)
     B.tq_decompress_aggregate(pays, params, out, bits, be)
     torch.cuda.synchronize()
     print("device path done", flush=True)
@@ -226,7 +226,7 @@ def test_group_counter_beyond_32_bits():
     from test_oracle_quantizer import make_params, NONUNIFORM_3
     P_all = np.concatenate([make_params(np.array(NONUNIFORM_3) * (1 + b % 3), O.GRID_NONUNIFORM) for b in range(nb)])
     pay = B.alloc_payload(d, bits)
-    B.tq_compress(g, B.params_from_numpy(P_all), pay, bits, 0xFEEDFACE, 3, 11, be)
+    B.tq_compress(g, B.params_from_numpy(P_all), pay, bits, 0xFEEDFACE, 3, 11, be, B.GRID_NONUNIFORM)
     torch.cuda.synchronize()
     print("compressed", flush=True)
     rng = np.random.default_rng(3)
