@@ -86,6 +86,13 @@ def lib():
                                                       C.c_void_p, C.c_void_p]
         L.tqo_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                      C.c_int, C.c_void_p]
+        L.tqo_stats_segments.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_void_p, C.c_uint64,
+                                         C.c_float, C.c_void_p]
+        L.tqo_compress_segments.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_void_p, C.c_uint64,
+                                            C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p]
+        L.tqo_decompress_aggregate_segments.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                                        C.c_uint64, C.c_void_p, C.c_uint64, C.c_int,
+                                                        C.c_int, C.c_void_p]
         L.tqo_sizeof_stats.restype = C.c_size_t
         L.tqo_sizeof_params.restype = C.c_size_t
         assert L.tqo_sizeof_stats() == STATS_DTYPE.itemsize
@@ -255,4 +262,50 @@ def dequantize(payload, params, d, bits, bucket_elems=0):
     out = np.zeros(d, dtype=np.float32)
     _check(lib().tqo_dequantize(_ptr(payload), _ptr(params), d, bucket_elems, bits,
                                 _ptr(out)), "tqo_dequantize")
+    return out
+
+
+def _offsets(seg_offsets, d):
+    off = np.ascontiguousarray(seg_offsets, dtype=np.uint64)
+    assert off.ndim == 1 and off.size >= 2 and int(off[-1]) == d
+    return off
+
+
+def stats_segments(g, seg_offsets, g_min=0.0):
+    """One STATS_DTYPE record per segment [seg_offsets[s], seg_offsets[s+1])."""
+    g = np.ascontiguousarray(g)
+    off = _offsets(seg_offsets, g.size)
+    out = np.zeros(off.size - 1, dtype=STATS_DTYPE)
+    _check(lib().tqo_stats_segments(_ptr(g), _dtype_code(g), g.size, _ptr(off), off.size - 1,
+                                    float(g_min), _ptr(out)), "tqo_stats_segments")
+    return out
+
+
+def compress_segments(g, seg_offsets, params, seed, worker, step):
+    g = np.ascontiguousarray(g)
+    off = _offsets(seg_offsets, g.size)
+    params = np.ascontiguousarray(params, dtype=PARAMS_DTYPE).reshape(-1)
+    assert params.size == off.size - 1
+    bits = int(params["bits"][0])
+    out = np.zeros(payload_bytes(g.size, bits), dtype=np.uint8)
+    _check(lib().tqo_compress_segments(_ptr(g), _dtype_code(g), g.size, _ptr(off), off.size - 1,
+                                       _ptr(params), seed, worker, step, _ptr(out)),
+           "tqo_compress_segments")
+    return out
+
+
+def decompress_aggregate_segments(payloads, params, d, seg_offsets, bits, weights=None, out=None):
+    N = len(payloads)
+    off = _offsets(seg_offsets, d)
+    payloads = [np.ascontiguousarray(p, dtype=np.uint8) for p in payloads]
+    params = [np.ascontiguousarray(p, dtype=PARAMS_DTYPE).reshape(-1) for p in params]
+    pp = (C.c_void_p * N)(*[p.ctypes.data for p in payloads])
+    qq = (C.c_void_p * N)(*[p.ctypes.data for p in params])
+    w = None if weights is None else np.ascontiguousarray(weights, dtype=np.float32)
+    accumulate = out is not None
+    if out is None:
+        out = np.zeros(d, dtype=np.float32)
+    _check(lib().tqo_decompress_aggregate_segments(pp, qq, None if w is None else _ptr(w), N, d,
+                                                   _ptr(off), off.size - 1, bits, int(accumulate),
+                                                   _ptr(out)), "tqo_decompress_aggregate_segments")
     return out

@@ -21,6 +21,8 @@
  *   tqo_decompress_aggregate_update  ... followed by theta <- theta - eta g_bar
  *   tqo_stats               Sec. V (MLE of the tail index), Sec. IV (rho,
  *                           Q_U, integral of p^(1/3)): the raw reductions
+ *   tqo_*_segments          the same three steps with one (alpha, codebook) per
+ *                           variable-size segment (Sec. V: layers quantized independently)
  * The parameter design of Sec. IV (alpha fixed points, level tables) lives in
  * params.py beside this file, in fp64.
  *
@@ -438,6 +440,86 @@ int tqo_dequantize(const uint8_t *payload, const tqo_params_t *params,
     if (check_layout(d, bucket_elems) || bits < 2 || bits > 4) return TQO_EINVAL;
     for (uint64_t e = 0; e < d; ++e)
         out[e] = params[bucket_of(e, bucket_elems)].level[read_code(payload, e, (uint32_t)bits)];
+    return TQO_OK;
+}
+
+
+/* ---------------------------------------------------- variable-size segments -- */
+
+/* Sec. V quantizes the layers of a network independently ("per layer type"): here the flat
+ * gradient is cut at seg_offsets[0] = 0 < seg_offsets[1] < ... < seg_offsets[nseg] = d into
+ * nseg segments (interior offsets multiples of 128), each with its own statistics record and
+ * its own (alpha, codebook).  Everything else is as in the bucketed functions above: the
+ * element index that keys the random draws and the bit position in the payload are those of
+ * the flat gradient. */
+static int check_segments(uint64_t d, const uint64_t *off, uint64_t nseg)
+{
+    if (d == 0 || nseg == 0 || off[0] != 0 || off[nseg] != d) return TQO_EINVAL;
+    for (uint64_t s = 0; s < nseg; ++s) {
+        if (off[s + 1] <= off[s]) return TQO_EINVAL;
+        if (s + 1 < nseg && off[s + 1] % 128 != 0) return TQO_EINVAL;
+    }
+    return TQO_OK;
+}
+
+int tqo_stats_segments(const void *g, int dtype, uint64_t d, const uint64_t *seg_offsets,
+                       uint64_t nseg, float g_min, tqo_stats_t *stats)
+{
+    if (check_segments(d, seg_offsets, nseg) || (dtype != TQO_F32 && dtype != TQO_BF16))
+        return TQO_EINVAL;
+    const size_t esz = dtype == TQO_F32 ? 4 : 2;
+    for (uint64_t s = 0; s < nseg; ++s) {
+        /* a segment on its own is a tensor with one bucket */
+        const uint64_t lo = seg_offsets[s], n = seg_offsets[s + 1] - lo;
+        if (tqo_stats((const char *)g + lo * esz, dtype, n, 0, g_min, &stats[s])) return TQO_EINVAL;
+    }
+    return TQO_OK;
+}
+
+int tqo_compress_segments(const void *g, int dtype, uint64_t d, const uint64_t *seg_offsets,
+                          uint64_t nseg, const tqo_params_t *params, uint64_t seed,
+                          uint32_t worker, uint32_t step, uint8_t *payload)
+{
+    if (check_segments(d, seg_offsets, nseg) || (dtype != TQO_F32 && dtype != TQO_BF16))
+        return TQO_EINVAL;
+    const uint32_t bits = params[0].bits;
+    if (bits < 2 || bits > 4) return TQO_EINVAL;
+    memset(payload, 0, tqo_payload_bytes(d, (int)bits));
+    for (uint64_t s = 0; s < nseg; ++s) {
+        const tqo_params_t *P = &params[s];
+        if (P->bits != bits || P->s != (1u << bits) - 1u) return TQO_EINVAL;
+        for (uint64_t e = seg_offsets[s]; e < seg_offsets[s + 1]; ++e) {
+            uint32_t r = tqo_rand16(seed, worker, step, e);
+            uint32_t code = tqo_quantize_one(load_elem(g, dtype, e), P, r);
+            uint64_t bitpos = e * bits;
+            for (uint32_t t = 0; t < bits; ++t, ++bitpos)
+                if ((code >> t) & 1u) payload[bitpos >> 3] |= (uint8_t)(1u << (bitpos & 7));
+        }
+    }
+    return TQO_OK;
+}
+
+int tqo_decompress_aggregate_segments(const uint8_t *const *payload,
+                                      const tqo_params_t *const *params, const float *weights,
+                                      int N, uint64_t d, const uint64_t *seg_offsets,
+                                      uint64_t nseg, int bits, int accumulate, float *out)
+{
+    if (check_segments(d, seg_offsets, nseg) || N < 1 || bits < 2 || bits > 4) return TQO_EINVAL;
+    const float w_uniform = 1.0f / (float)N;
+    for (uint64_t s = 0; s < nseg; ++s) {
+        for (uint64_t e = seg_offsets[s]; e < seg_offsets[s + 1]; ++e) {
+            float acc = 0.0f;
+            for (int i = 0; i < N; ++i) {
+                const tqo_params_t *P = &params[i][s];
+                if ((int)P->bits != bits) return TQO_EINVAL;
+                float term = P->level[read_code(payload[i], e, (uint32_t)bits)];
+                if (weights) term = weights[i] * term;
+                acc = (i == 0) ? term : acc + term;
+            }
+            if (!weights) acc = acc * w_uniform;
+            out[e] = accumulate ? out[e] + acc : acc;
+        }
+    }
     return TQO_OK;
 }
 
