@@ -59,6 +59,8 @@ def parse():
     ap.add_argument("--other-configs", default="all", choices=["all", "none"],
                     help="also time the other variants of the benchmark plan (reported under `configs`)")
     ap.add_argument("--other-steps", type=int, default=20, help="timed steps of each other variant")
+    ap.add_argument("--segments", action="store_true",
+                    help="one record per layer of the workload's recipe (the *_segments entry points)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="profiling aid: only run device-to-device copies of 1 GiB, the known-size "
@@ -71,7 +73,7 @@ def parse():
 class Path:
     """Device buffers of one workload and the launch sequence of one step."""
 
-    def __init__(self, wl, bits, grid, mode="batched", sets=2):
+    def __init__(self, wl, bits, grid, mode="batched", sets=2, segments=False):
         import torch
         from paper_2402_01798_amd import binding as B
         from paper_2402_01798_amd import synth
@@ -96,23 +98,41 @@ class Path:
         self.pay = [B.alloc_payload(self.d, bits) for _ in range(self.N)]
         self.out = torch.empty(self.d, dtype=torch.float32, device="cuda")
         self.step_no = 0
+        # per-layer quantization: one record per layer of the workload's recipe instead of per bucket,
+        # through the *_segments entry points (one launch per worker and stage)
+        self.seg = None
+        if segments:
+            self.seg = B.Segments(synth.layer_segments(wl, self.d))
+            self.mode = mode = "per-worker"
+            self.stats = [torch.empty(self.seg.nseg * B.STATS_BYTES, dtype=torch.uint8, device="cuda") for _ in range(self.N)]
+            self.params = [torch.empty(self.seg.nseg * B.PARAMS_BYTES, dtype=torch.uint8, device="cuda") for _ in range(self.N)]
+            self.ws = [torch.empty(B.stats_segments_workspace_bytes(self.d, self.seg.nseg), dtype=torch.uint8,
+                                   device="cuda")] * self.N
 
     def describe(self):
         torch = self.torch
-        return "%s: d=%d x N=%d workers, %s, b=%d, %s grid, bucket_elems=%d" % (
+        what = "bucket_elems=%d" % self.be if self.seg is None else "%d layer segments" % self.seg.nseg
+        return "%s: d=%d x N=%d workers, %s, b=%d, %s grid, %s" % (
             self.wl.name, self.d, self.N, "fp32" if self.wl.dtype == torch.float32 else "bf16", self.bits,
-            "uniform" if self.grid == 0 else "non-uniform", self.be)
+            "uniform" if self.grid == 0 else "non-uniform", what)
 
     def stats_i(self, i):
+        if self.seg is not None:
+            return self.B.tq_stats_segments(self.g[i], self.seg, self.stats[i], self.ws[i], self.wl.g_min)
         self.B.tq_stats(self.g[i], self.stats[i], self.ws[i], self.be, self.wl.g_min)
 
     def params_i(self, i):
         self.B.tq_params(self.stats[i], self.params[i], self.bits, self.grid)
 
     def compress_i(self, i):
+        if self.seg is not None:
+            return self.B.tq_compress_segments(self.g[i], self.seg, self.params[i], self.pay[i], self.bits, 0x5EED, i,
+                                               self.step_no)
         self.B.tq_compress(self.g[i], self.params[i], self.pay[i], self.bits, 0x5EED, i, self.step_no, self.be, self.grid)
 
     def decode(self):
+        if self.seg is not None:
+            return self.B.tq_decompress_aggregate_segments(self.pay, self.params, self.seg, self.out, self.bits)
         self.B.tq_decompress_aggregate(self.pay, self.params, self.out, self.bits, self.be)
 
     def stats_all(self):
@@ -347,13 +367,13 @@ def main():
     wl = synth.WORKLOADS[a.workload]
     bits = a.bits or wl.bits[0]
     grid = a.grid if a.grid >= 0 else wl.grids[0]
-    path = Path(wl, bits, grid, a.launch, max(1, a.buffer_sets))
+    path = Path(wl, bits, grid, a.launch, max(1, a.buffer_sets), segments=a.segments)
     torch.cuda.synchronize()
 
     if a.kernel_only:
         # profiling aid: the named entry point alone (after one full step so its inputs exist)
         path.step()
-        if a.launch == "batched":
+        if path.mode == "batched":
             fn = {"stats": path.stats_all, "params": path.params_all, "compress": path.compress_all,
                   "decode": path.decode}[a.kernel_only]
         else:
@@ -385,7 +405,7 @@ def main():
         "cold": res.get("cold"),
         "roofline": compress_roofline(path, res),
     }
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and not a.segments:
         out["cpu_baseline"] = cpu_baseline(path)
 
     if a.other_configs == "all" and a.launch == "batched":
@@ -404,6 +424,15 @@ def main():
             others["%s/b%d/%s" % (name, b, "uniform" if g == 0 else "nonuniform")] = r
             del p2
             torch.cuda.empty_cache()
+        # config 4 once more with one record per LAYER of its recipe (variable-size segments)
+        p2 = Path(synth.WORKLOADS["cfg4"], 2, 0, "per-worker", max(1, a.buffer_sets), segments=True)
+        torch.cuda.synchronize()
+        r = measure(p2, a.other_steps, 3, 0)
+        r["roofline"] = compress_roofline(p2, r)
+        r["roofline"]["kernel"] = "tq_compress_segments_kernel"
+        others["cfg4/b2/uniform/layer-segments"] = r
+        del p2
+        torch.cuda.empty_cache()
         out["configs"] = others
     print(json.dumps(out))
 

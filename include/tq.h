@@ -239,6 +239,40 @@ int tq_quantize_dequantize(const void* g_dev, int dtype, uint64_t d, uint64_t bu
                            uint32_t worker, uint32_t step, int accumulate, float* out_dev,
                            void* stream);
 
+/*
+ * Variable-size segments -- Sec. V quantizes the layers of a network independently: the flat
+ * gradient is cut into nseg consecutive segments of any sizes, each with its own statistics
+ * record and its own (alpha, codebook), in one launch per step instead of one call per layer.
+ * tq_params is used as it is, with nb = nseg.  Payload, random draws and aggregate are those of
+ * the bucketed calls: only the record an element is encoded with changes.
+ *   seg_offsets_dev   [nseg + 1] device array (8-byte aligned): 0 = off[0] < off[1] < ... <
+ *                     off[nseg] = d, every interior offset a multiple of 128
+ *   seg_offsets_host  the same table in host memory, or NULL.  When given it is checked
+ *                     before anything is enqueued (TQ_EINVAL if malformed); keeping the two
+ *                     copies equal is the caller's business.  The kernels bound every access
+ *                     by d and nseg themselves, so a malformed device table gives wrong
+ *                     results, never an access outside the caller's buffers.
+ *   stats_dev / params_dev  [nseg] records
+ *   workspace_dev     tq_stats_segments_workspace_bytes(d, nseg) bytes, rules as for tq_stats
+ * tq_compress_segments takes no `grid`: it has one launch shape.  The segment kernels favour
+ * generality over the last tenth of speed (one tile per workgroup, plain level tables).
+ */
+uint64_t tq_stats_segments_workspace_bytes(uint64_t d, uint64_t nseg);
+int tq_stats_segments(const void* g_dev, int dtype, uint64_t d, const uint64_t* seg_offsets_dev,
+                      const uint64_t* seg_offsets_host, uint64_t nseg, float g_min,
+                      tq_stats_t* stats_dev, void* workspace_dev, uint64_t workspace_bytes,
+                      void* stream);
+int tq_compress_segments(const void* g_dev, int dtype, uint64_t d, const uint64_t* seg_offsets_dev,
+                         const uint64_t* seg_offsets_host, uint64_t nseg,
+                         const tq_params_t* params_dev, int bits, uint64_t seed, uint32_t worker,
+                         uint32_t step, void* payload_dev, void* stream);
+int tq_decompress_aggregate_segments(const void* const* payload_host,
+                                     const tq_params_t* const* params_host,
+                                     const float* weights_host, int N, uint64_t d,
+                                     const uint64_t* seg_offsets_dev,
+                                     const uint64_t* seg_offsets_host, uint64_t nseg, int bits,
+                                     int accumulate, float* out_dev, void* stream);
+
 /* Text for a return code (static storage). */
 const char* tq_strerror(int code);
 

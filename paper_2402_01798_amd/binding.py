@@ -72,6 +72,13 @@ def lib():
         L.tq_stats_multi.argtypes = [vp, i32, i32, u64, u64, f32, vp, vp, u64, vp]
         L.tq_params_multi.argtypes = [vp, i32, u64, i32, i32, f32, vp, vp]
         L.tq_compress_multi.argtypes = [vp, i32, i32, u64, u64, vp, i32, i32, u64, u32, u32, vp, vp]
+        L.tq_stats_segments_workspace_bytes.argtypes = [u64, u64]
+        L.tq_stats_segments_workspace_bytes.restype = u64
+        L.tq_stats_segments.argtypes = [vp, i32, u64, vp, vp, u64, f32, vp, vp, u64, vp]
+        L.tq_compress_segments.argtypes = [vp, i32, u64, vp, vp, u64, vp, i32, u64, u32, u32, vp, vp]
+        L.tq_decompress_aggregate_segments.argtypes = [vp, vp, vp, i32, u64, vp, vp, u64, i32, i32, vp, vp]
+        for f in (L.tq_stats_segments, L.tq_compress_segments, L.tq_decompress_aggregate_segments):
+            f.restype = i32
         for f in (L.tq_stats, L.tq_stats_static, L.tq_params, L.tq_compress, L.tq_decompress_aggregate,
                   L.tq_decompress_aggregate_update, L.tq_stats_multi, L.tq_params_multi, L.tq_compress_multi):
             f.restype = i32
@@ -256,6 +263,60 @@ def tq_decompress_aggregate_update(payloads, params, theta, bits, eta, momentum=
         _dev(theta, "theta"), None if velocity is None else _dev(velocity, "velocity"), _stream()),
         "tq_decompress_aggregate_update")
     return theta
+
+
+class Segments:
+    """A segment table in both memories: ``offsets`` (host, numpy uint64, nseg + 1 entries) and
+    its device copy.  Pure marshalling: the library checks the host copy."""
+
+    def __init__(self, offsets, device="cuda"):
+        self.host = np.ascontiguousarray(offsets, dtype=np.uint64)
+        self.dev = torch.from_numpy(self.host.view(np.int64).copy()).to(device)
+        self.nseg = self.host.size - 1
+        self.d = int(self.host[-1])
+
+    def args(self):
+        return C.c_void_p(self.dev.data_ptr()), self.host.ctypes.data_as(C.c_void_p), self.nseg
+
+
+def stats_segments_workspace_bytes(d, nseg):
+    return int(lib().tq_stats_segments_workspace_bytes(d, nseg))
+
+
+def tq_stats_segments(g, seg, stats, workspace, g_min=0.0):
+    dev, host, nseg = seg.args()
+    _check(lib().tq_stats_segments(_dev(g, "g"), _dtype_code(g), g.numel(), dev, host, nseg, g_min,
+                                   _dev(stats, "stats"), _dev(workspace, "workspace"), workspace.numel(),
+                                   _stream()), "tq_stats_segments")
+    return stats
+
+
+def tq_compress_segments(g, seg, params, payload, bits, seed, worker, step):
+    d = g.numel()
+    if params.numel() != seg.nseg * PARAMS_BYTES or payload.numel() < payload_bytes(d, bits):
+        raise ValueError("params / payload buffer size does not match the segments")
+    dev, host, nseg = seg.args()
+    _check(lib().tq_compress_segments(_dev(g, "g"), _dtype_code(g), d, dev, host, nseg, _dev(params, "params"),
+                                      bits, seed, worker, step, _dev(payload, "payload"), _stream()),
+           "tq_compress_segments")
+    return payload
+
+
+def tq_decompress_aggregate_segments(payloads, params, seg, out, bits, weights=None, accumulate=False):
+    d = out.numel()
+    if out.dtype != torch.float32:
+        raise TypeError("out must be float32")
+    N = len(payloads)
+    for p, q in zip(payloads, params):
+        if p.numel() < payload_bytes(d, bits) or q.numel() != seg.nseg * PARAMS_BYTES:
+            raise ValueError("payload / params buffer size does not match the segments")
+    pp = (C.c_void_p * N)(*[_dev(p, "payload").value for p in payloads])
+    qq = (C.c_void_p * N)(*[_dev(q, "params").value for q in params])
+    ww = None if weights is None else (C.c_float * N)(*[float(w) for w in weights])
+    dev, host, nseg = seg.args()
+    _check(lib().tq_decompress_aggregate_segments(pp, qq, ww, N, d, dev, host, nseg, bits, int(bool(accumulate)),
+                                                  _dev(out, "out"), _stream()), "tq_decompress_aggregate_segments")
+    return out
 
 
 def stats_to_numpy(stats):

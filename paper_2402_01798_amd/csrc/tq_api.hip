@@ -22,6 +22,16 @@ hipError_t tq_launch_simulate(const void* g, int dtype, uint64_t d, uint64_t buc
                               int bits, uint64_t seed, uint32_t worker, uint32_t step, int accumulate, float* out,
                               hipStream_t st);
 
+uint64_t tq_stats_segments_workspace_bytes_impl(uint64_t d, uint64_t nseg);
+hipError_t tq_launch_stats_segments(const void* g, int dtype, uint64_t d, const uint64_t* seg_off, uint64_t nseg,
+                                    float g_min, tq_stats_t* stats, void* workspace, hipStream_t st);
+hipError_t tq_launch_compress_segments(const void* g, int dtype, uint64_t d, const uint64_t* seg_off, uint64_t nseg,
+                                       const tq_params_t* params, int bits, uint64_t seed, uint32_t worker,
+                                       uint32_t step, void* payload, hipStream_t st);
+hipError_t tq_launch_decode_segments(const void* const* payload, const tq_params_t* const* params,
+                                     const float* weights, int N, uint64_t d, const uint64_t* seg_off,
+                                     uint64_t nseg, int bits, int accumulate, float* out, hipStream_t st);
+
 static_assert(sizeof(tq_stats_t) == 3632, "tq_stats_t layout is part of the interface");
 static_assert(sizeof(tq_params_t) == 160, "tq_params_t layout is part of the interface");
 
@@ -211,6 +221,69 @@ int tq_decompress_aggregate_update(const void* const* payload_host, const tq_par
     return from_hip(tq_launch_decode(payload_host, params_host, weights_host, N, d, bucket_elems, bits,
                                      velocity_dev ? 3 : 2, eta, momentum, weight_decay, velocity_dev, theta_dev,
                                      static_cast<hipStream_t>(stream)));
+}
+
+// Checks shared by the three segment calls: sizes, the device table's alignment and, when the
+// caller also passes the table in host memory, the table itself.
+static int check_segments(uint64_t d, const uint64_t* seg_dev, const uint64_t* seg_host, uint64_t nseg)
+{
+    if (d == 0 || nseg == 0 || !seg_dev) return TQ_EINVAL;
+    if (d > (1ull << 40) || nseg > 0xFFFFFFFFull) return TQ_EUNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(seg_dev) & 7u) return TQ_EALIGN;
+    if (seg_host) {
+        if (seg_host[0] != 0 || seg_host[nseg] != d) return TQ_EINVAL;
+        for (uint64_t s = 0; s < nseg; ++s) {
+            if (seg_host[s + 1] <= seg_host[s]) return TQ_EINVAL;
+            if (s + 1 < nseg && seg_host[s + 1] % 128 != 0) return TQ_EINVAL;
+        }
+    }
+    return TQ_OK;
+}
+
+uint64_t tq_stats_segments_workspace_bytes(uint64_t d, uint64_t nseg)
+{
+    if (d == 0 || nseg == 0 || d > (1ull << 40) || nseg > 0xFFFFFFFFull) return 0;
+    return tq_stats_segments_workspace_bytes_impl(d, nseg);
+}
+
+int tq_stats_segments(const void* g_dev, int dtype, uint64_t d, const uint64_t* seg_offsets_dev,
+                      const uint64_t* seg_offsets_host, uint64_t nseg, float g_min, tq_stats_t* stats_dev,
+                      void* workspace_dev, uint64_t workspace_bytes, void* stream)
+{
+    int rc;
+    if ((rc = check_segments(d, seg_offsets_dev, seg_offsets_host, nseg)) || (rc = check_dtype(dtype))) return rc;
+    if (!g_dev || !stats_dev || !workspace_dev) return TQ_EINVAL;
+    if (workspace_bytes < tq_stats_segments_workspace_bytes_impl(d, nseg)) return TQ_EINVAL;
+    if (g_min != g_min || (g_min > 0.0f && g_min < 9.094947017729282e-13f) || g_min > 3.0e38f) return TQ_EINVAL;
+    if (!aligned16(g_dev) || !aligned16(stats_dev) || !aligned16(workspace_dev)) return TQ_EALIGN;
+    return from_hip(tq_launch_stats_segments(g_dev, dtype, d, seg_offsets_dev, nseg, g_min, stats_dev, workspace_dev,
+                                             static_cast<hipStream_t>(stream)));
+}
+
+int tq_compress_segments(const void* g_dev, int dtype, uint64_t d, const uint64_t* seg_offsets_dev,
+                         const uint64_t* seg_offsets_host, uint64_t nseg, const tq_params_t* params_dev, int bits,
+                         uint64_t seed, uint32_t worker, uint32_t step, void* payload_dev, void* stream)
+{
+    int rc;
+    if ((rc = check_segments(d, seg_offsets_dev, seg_offsets_host, nseg)) || (rc = check_dtype(dtype)) ||
+        (rc = check_bits(bits)))
+        return rc;
+    if (!g_dev || !params_dev || !payload_dev) return TQ_EINVAL;
+    if (!aligned16(g_dev) || !aligned16(params_dev) || !aligned16(payload_dev)) return TQ_EALIGN;
+    return from_hip(tq_launch_compress_segments(g_dev, dtype, d, seg_offsets_dev, nseg, params_dev, bits, seed, worker,
+                                                step, payload_dev, static_cast<hipStream_t>(stream)));
+}
+
+int tq_decompress_aggregate_segments(const void* const* payload_host, const tq_params_t* const* params_host,
+                                     const float* weights_host, int N, uint64_t d, const uint64_t* seg_offsets_dev,
+                                     const uint64_t* seg_offsets_host, uint64_t nseg, int bits, int accumulate,
+                                     float* out_dev, void* stream)
+{
+    int rc;
+    if ((rc = check_segments(d, seg_offsets_dev, seg_offsets_host, nseg))) return rc;
+    if ((rc = check_decode(payload_host, params_host, weights_host, N, d, 0, bits, out_dev))) return rc;
+    return from_hip(tq_launch_decode_segments(payload_host, params_host, weights_host, N, d, seg_offsets_dev, nseg,
+                                              bits, accumulate ? 1 : 0, out_dev, static_cast<hipStream_t>(stream)));
 }
 
 const char* tq_strerror(int code)

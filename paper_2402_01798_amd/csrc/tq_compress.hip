@@ -319,6 +319,73 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     }
 }
 
+// tq_compress_segments: the same client step with one (alpha, codebook) per variable-size
+// segment of the flat gradient (Sec. V: the layers of a network are quantized independently).
+// One tile of 2048 elements per workgroup, wherever the segments fall: the workgroup finds the
+// segment its tile starts in and takes the segments that overlap the tile one after the other
+// (a lane's group of 8 lies in exactly one, the offsets being multiples of 128); large layers
+// are the rule, so almost every workgroup makes one pass.  The last segment also owns the
+// padding up to a multiple of 128 elements.  No access depends on the table being well-formed:
+// the segment index stays inside [0, nseg) and every element access is bounded by d.
+template <int DTYPE, int BITS>
+__global__ __launch_bounds__(kBlock) void tq_compress_segments_kernel(
+    const void* __restrict__ g, uint64_t d, uint64_t d_pad, const uint64_t* __restrict__ seg_off, uint32_t nseg,
+    const tq_params_t* __restrict__ params, uint32_t seed_lo, uint32_t seed_hi, uint32_t worker, uint32_t step,
+    uint8_t* __restrict__ payload, uint64_t payload_bytes)
+{
+    const uint64_t ebase = (uint64_t)linear_block() * kTile;
+    if (ebase >= d_pad) return;                                // padding of a folded grid
+    const uint64_t tile_end = ebase + kTile < d_pad ? ebase + kTile : d_pad;
+    const uint32_t lane = threadIdx.x;
+    const uint64_t e0 = ebase + (uint64_t)lane * kGroup;
+    const uint64_t byte_off = (e0 >> 3) * (uint64_t)BITS;
+    __shared__ LevelLds tab;
+
+    uint32_t s = find_segment(seg_off, nseg, ebase < d ? ebase : d - 1);
+    for (;;) {
+        const uint64_t seg_lo = seg_off[s];
+        const uint64_t seg_hi = s + 1 < nseg ? seg_off[s + 1] : d_pad;
+        const tq_params_t* P = params + s;
+        float lv[16];
+        const float alpha = P->alpha;
+        const float inv_step = P->inv_w[0];
+        const bool nonuniform = P->grid != TQ_GRID_UNIFORM;    // uniform over the workgroup
+        if (nonuniform) {
+            fill_level_lds(tab, P, (1u << BITS) - 1u);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) lv[j] = P->level[j];   // wave-uniform: scalar loads
+            __syncthreads();
+        }
+        if (e0 >= seg_lo && e0 < seg_hi && e0 < tile_end && byte_off < payload_bytes) {
+            uint32_t word = 0;                                 // a group wholly in the padding encodes as 0
+            if (e0 < d) {
+                const int n_valid = d - e0 >= (uint64_t)kGroup ? kGroup : (int)(d - e0);
+                float x[8];
+                if (n_valid == kGroup) {
+                    load_group<DTYPE, false>(g, e0, x);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, e0 + j) : 0.0f;
+                }
+                const uint64_t q = e0 >> 3;
+                uint32_t rw[4];
+                philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), worker, step, seed_lo, seed_hi, rw);
+                replace_nan(x);
+                if (n_valid == kGroup)
+                    word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab)
+                                      : encode_group<BITS, TQ_GRID_UNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab);
+                else
+                    word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab)
+                                      : encode_group<BITS, TQ_GRID_UNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab);
+            }
+            store_codes<BITS>(payload + byte_off, word, payload_bytes - byte_off);
+        }
+        if (seg_hi >= tile_end || s + 1 >= nseg) break;
+        ++s;
+        __syncthreads();                                       // before the next segment's table replaces this one
+    }
+}
+
 // tq_quantize_dequantize: out[e] = Q[T_alpha(g[e])] as the server would reconstruct it from
 // this worker's message (the level of the code tq_compress_kernel would have written: same
 // draws, same arithmetic), without the round trip through a payload.  One tile per workgroup.
@@ -484,5 +551,33 @@ hipError_t tq_launch_simulate(const void* g, int dtype, uint64_t d, uint64_t buc
     if (dtype == TQ_F32) { TQ_LAUNCH_SIM_B(TQ_F32) } else { TQ_LAUNCH_SIM_B(TQ_BF16) }
 #undef TQ_LAUNCH_SIM_B
 #undef TQ_LAUNCH_SIM
+    return hipGetLastError();
+}
+
+
+// Host side of tq_compress_segments after the argument checks of the C entry point.
+hipError_t tq_launch_compress_segments(const void* g, int dtype, uint64_t d, const uint64_t* seg_off, uint64_t nseg,
+                                       const tq_params_t* params, int bits, uint64_t seed, uint32_t worker,
+                                       uint32_t step, void* payload, hipStream_t st)
+{
+    const uint64_t d_pad = (d + 127) / 128 * 128;
+    const uint64_t nblocks = (d_pad + tq::kTile - 1) / tq::kTile;
+    dim3 blocks;
+    if (nseg > 0xFFFFFFFFull || !tq::fold_grid(nblocks, tq::kBlock, 1, blocks)) return hipErrorInvalidValue;
+    const uint32_t slo = (uint32_t)seed, shi = (uint32_t)(seed >> 32);
+    const uint64_t pbytes = tq_payload_bytes(d, bits);
+    const dim3 threads(tq::kBlock);
+#define TQ_LAUNCH_CSEG(DT, B)                                                                                  \
+    hipLaunchKernelGGL((tq::tq_compress_segments_kernel<DT, B>), blocks, threads, 0, st, g, d, d_pad, seg_off, \
+                       (uint32_t)nseg, params, slo, shi, worker, step, static_cast<uint8_t*>(payload), pbytes)
+#define TQ_LAUNCH_CSEG_B(DT)                      \
+    switch (bits) {                               \
+        case 2: TQ_LAUNCH_CSEG(DT, 2); break;     \
+        case 3: TQ_LAUNCH_CSEG(DT, 3); break;     \
+        default: TQ_LAUNCH_CSEG(DT, 4); break;    \
+    }
+    if (dtype == TQ_F32) { TQ_LAUNCH_CSEG_B(TQ_F32) } else { TQ_LAUNCH_CSEG_B(TQ_BF16) }
+#undef TQ_LAUNCH_CSEG_B
+#undef TQ_LAUNCH_CSEG
     return hipGetLastError();
 }

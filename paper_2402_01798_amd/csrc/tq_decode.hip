@@ -351,6 +351,57 @@ __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
     else finish_ragged<MODE>(out + e0, e0, acc, (int)(d - e0), up);
 }
 
+// tq_decompress_aggregate_segments: the server step with one codebook per variable-size
+// segment (and worker).  Shape of tq_compress_segments_kernel: one tile per workgroup, the
+// segments that overlap it taken one after the other, each with the N workers' level rows of
+// that segment in LDS.
+template <int BITS, int MODE>
+__global__ __launch_bounds__(kBlock) void tq_decode_segments_kernel(
+    const DecodeArgs args, int N, int weighted, float scale, uint64_t d, uint64_t d_pad,
+    const uint64_t* __restrict__ seg_off, uint32_t nseg, uint64_t payload_bytes, float* __restrict__ out,
+    const Update up)
+{
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    const uint64_t ebase = (uint64_t)linear_block() * kTile;
+    if (ebase >= d) return;
+    const uint64_t tile_end = ebase + kTile < d_pad ? ebase + kTile : d_pad;
+    const uint64_t e0 = ebase + (uint64_t)threadIdx.x * kGroup;
+    __shared__ float table[TQ_MAX_WORKERS * 16];
+
+    uint32_t s = find_segment(seg_off, nseg, ebase);
+    for (;;) {
+        const uint64_t seg_lo = seg_off[s];
+        const uint64_t seg_hi = s + 1 < nseg ? seg_off[s + 1] : d_pad;
+        fill_level_rows(table, args, N, weighted, s);
+        __syncthreads();
+        if (e0 >= seg_lo && e0 < seg_hi && e0 < d) {
+            const CodeLoad cl = code_load(e0 >> 3, BITS, payload_bytes);
+            const bool whole = e0 + kGroup <= d;
+            float acc[8], prev[8], vel[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { acc[j] = 0.0f; prev[j] = 0.0f; vel[j] = 0.0f; }
+            if (whole) {
+                if constexpr (MODE != kStore && MODE != kStoreStream) load8(out + e0, prev);
+            }
+            for (int i = 0; i < N; ++i) {
+                const uint32_t w = load_code_word<BITS>(args.payload[i], cl) >> cl.first_bit;
+                const float* row = table + i * 16;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] = acc[j] + row[(w >> (j * BITS)) & MASK];
+            }
+            if (!weighted) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j] = acc[j] * scale;
+            }
+            if (whole) finish_group<MODE>(out + e0, e0, acc, prev, vel, up);
+            else finish_ragged<MODE>(out + e0, e0, acc, (int)(d - e0), up);
+        }
+        if (seg_hi >= tile_end || s + 1 >= nseg) break;
+        ++s;
+        __syncthreads();                                       // before the next segment's rows replace these
+    }
+}
+
 }  // namespace tq
 
 namespace {
@@ -458,4 +509,40 @@ hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const
         case tq::kSgdMomentum: return launch_mode<tq::kSgdMomentum>(g, out, up, st);
         default: return hipErrorInvalidValue;
     }
+}
+
+
+// Host side of tq_decompress_aggregate_segments after the argument checks of the C entry point.
+hipError_t tq_launch_decode_segments(const void* const* payload, const tq_params_t* const* params,
+                                     const float* weights, int N, uint64_t d, const uint64_t* seg_off,
+                                     uint64_t nseg, int bits, int accumulate, float* out, hipStream_t st)
+{
+    tq::DecodeArgs args;
+    for (int i = 0; i < TQ_MAX_WORKERS; ++i) {
+        args.payload[i] = i < N ? static_cast<const uint8_t*>(payload[i]) : nullptr;
+        args.params[i] = i < N ? params[i] : nullptr;
+        args.weight[i] = (i < N && weights) ? weights[i] : 0.0f;
+    }
+    const uint64_t d_pad = (d + 127) / 128 * 128;
+    const uint64_t nblocks = (d + tq::kTile - 1) / tq::kTile;
+    dim3 blocks;
+    if (nseg > 0xFFFFFFFFull || !tq::fold_grid(nblocks, tq::kBlock, 1, blocks)) return hipErrorInvalidValue;
+    const uint64_t pbytes = tq_payload_bytes(d, bits);
+    const tq::Update up{0.0f, 0.0f, 0.0f, nullptr};
+    const float scale = 1.0f / (float)N;
+    const int weighted = weights ? 1 : 0;
+    const dim3 threads(tq::kBlock);
+#define TQ_LAUNCH_DSEG(B, M)                                                                                   \
+    hipLaunchKernelGGL((tq::tq_decode_segments_kernel<B, M>), blocks, threads, 0, st, args, N, weighted, scale, \
+                       d, d_pad, seg_off, (uint32_t)nseg, pbytes, out, up)
+#define TQ_LAUNCH_DSEG_M(B) \
+    if (accumulate) TQ_LAUNCH_DSEG(B, tq::kAccumulate); else TQ_LAUNCH_DSEG(B, tq::kStore)
+    switch (bits) {
+        case 2: TQ_LAUNCH_DSEG_M(2); break;
+        case 3: TQ_LAUNCH_DSEG_M(3); break;
+        default: TQ_LAUNCH_DSEG_M(4); break;
+    }
+#undef TQ_LAUNCH_DSEG_M
+#undef TQ_LAUNCH_DSEG
+    return hipGetLastError();
 }

@@ -88,6 +88,18 @@ inline bool fold_grid(uint64_t nblocks, unsigned threads, unsigned count, dim3& 
     return true;
 }
 
+// Variable-size segments: the largest s in [0, nseg) with seg_off[s] <= pos.  Every step reads
+// inside [0, nseg], whatever the table holds.
+__device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ seg_off, uint32_t nseg, uint64_t pos)
+{
+    uint32_t lo = 0, hi = nseg;
+    while (hi - lo > 1) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if (seg_off[mid] <= pos) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
 // Tile geometry shared by compress and decode.  Workgroup `blk` owns elements
 // [ebase, ebase + kTile) of bucket `bucket`, cut at `eend` (the bucket's end, the last
 // bucket's end being d rounded up to a multiple of 128 so the payload padding is covered).

@@ -109,32 +109,23 @@ __device__ __forceinline__ void write_scalars(tq_stats_t* S, const StatsExtra& x
     S->sum_log_tail = sum_log;
 }
 
+// LDS of one workgroup of the statistics kernels.
+struct StatsLds {
+    uint32_t hist[kStatsReplicas * kStatsStride];
+    uint32_t red_u32[2][kStatsBlock / 64];
+    unsigned long long red_u64[3][kStatsBlock / 64];
+};
+
+// One workgroup (kStatsBlock threads) takes the elements [cstart, cend) of one tensor: their
+// histogram goes to `row` (TQ_NBINS counts, every bin written), and thread 0 returns the other
+// sums (meaningless in the other threads).  cstart is a multiple of 8 elements.
 template <int DTYPE, bool TAIL>
-__global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
-    const PtrTable g_tab, uint64_t d, uint64_t bucket_elems, uint32_t slices, uint64_t slice_elems,
-    float g_min, char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes,
-    const MutPtrTable stats_tab)
+__device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, uint64_t cstart, uint64_t cend,
+                                                  float g_min, StatsLds& L, uint32_t* __restrict__ row)
 {
-    // blockIdx.y = tensor of the batch; each tensor has its own region of the workspace
-    const void* __restrict__ g = g_tab.p[blockIdx.y];
-    char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
-    uint32_t* __restrict__ ws_hist = reinterpret_cast<uint32_t*>(my_ws);
-    StatsExtra* __restrict__ ws_extra = reinterpret_cast<StatsExtra*>(my_ws + ws_hist_bytes);
-    const uint32_t blk = linear_block();
-    if ((uint64_t)(blk / slices) * bucket_elems >= d) return;          // padding of a folded grid
-    __shared__ uint32_t hist[kStatsReplicas * kStatsStride];
-    __shared__ uint32_t red_u32[2][kStatsBlock / 64];
-    __shared__ unsigned long long red_u64[3][kStatsBlock / 64];
+    uint32_t* hist = L.hist;
     for (int i = threadIdx.x; i < kStatsReplicas * kStatsStride; i += kStatsBlock) hist[i] = 0u;
     __syncthreads();
-
-    const uint32_t bucket = blk / slices;
-    const uint32_t slice = blk - bucket * slices;
-    const uint64_t bstart = (uint64_t)bucket * bucket_elems;
-    const uint64_t bend = bstart + bucket_elems < d ? bstart + bucket_elems : d;
-    uint64_t cstart = bstart + (uint64_t)slice * slice_elems;
-    cstart = cstart < bend ? cstart : bend;
-    const uint64_t cend = cstart + slice_elems < bend ? cstart + slice_elems : bend;
 
     uint32_t* my_hist = hist + (threadIdx.x & (kStatsReplicas - 1)) * kStatsStride;
     const uint32_t gmin_bits = __float_as_uint(g_min);
@@ -250,12 +241,7 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     if (not_counted) atomicSub(&my_hist[0], not_counted);
     __syncthreads();
 
-    // partial counts of this slice, every bin (the workspace is not pre-cleared), one
-    // contiguous row per workgroup; a bucket that is one slice writes its record directly and
-    // no second kernel follows
-    const bool final_record = slices == 1u;
-    tq_stats_t* S = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]) + bucket;
-    uint32_t* row = final_record ? S->hist : ws_hist + ((uint64_t)bucket * slices + slice) * TQ_NBINS;
+    // the slice's counts, every bin (the destination is not pre-cleared)
     for (int b = threadIdx.x; b < TQ_NBINS; b += kStatsBlock) {
         uint32_t total = 0u;
 #pragma unroll
@@ -263,25 +249,59 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
         row[b] = total;
     }
 
-    // max, counts and log-sum of this slice: wavefront reduction, then lane 0 adds the 8 waves
+    // max, counts and log-sum of the slice: wavefront reduction, then thread 0 adds the 8 waves
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     amax_bits = wave_reduce_max(amax_bits);
     nonfinite = wave_reduce_add(nonfinite);
     const unsigned long long nt = wave_reduce_add((unsigned long long)n_tail);
     const unsigned long long es = wave_reduce_add((unsigned long long)exp_acc);
     const unsigned long long lf = wave_reduce_add(log2m_fix);
-    if (lane == 0) { red_u32[0][wave] = amax_bits; red_u32[1][wave] = nonfinite; red_u64[0][wave] = nt; red_u64[1][wave] = es; red_u64[2][wave] = lf; }
+    if (lane == 0) { L.red_u32[0][wave] = amax_bits; L.red_u32[1][wave] = nonfinite; L.red_u64[0][wave] = nt; L.red_u64[1][wave] = es; L.red_u64[2][wave] = lf; }
     __syncthreads();
+    StatsExtra x{0u, 0u, 0ull, 0ll, 0ull};
     if (threadIdx.x == 0) {
-        StatsExtra x{0u, 0u, 0ull, 0ll, 0ull};
         for (int w = 0; w < kStatsBlock / 64; ++w) {
-            x.absmax_bits = red_u32[0][w] > x.absmax_bits ? red_u32[0][w] : x.absmax_bits;
-            x.n_nonfinite += red_u32[1][w];
-            x.n_tail += red_u64[0][w];
-            x.exp_sum += (long long)red_u64[1][w];
-            x.log2m_fix += red_u64[2][w];
+            x.absmax_bits = L.red_u32[0][w] > x.absmax_bits ? L.red_u32[0][w] : x.absmax_bits;
+            x.n_nonfinite += L.red_u32[1][w];
+            x.n_tail += L.red_u64[0][w];
+            x.exp_sum += (long long)L.red_u64[1][w];
+            x.log2m_fix += L.red_u64[2][w];
         }
         x.exp_sum -= 127ll * (long long)x.n_tail;                      // biased -> unbiased exponents
+    }
+    return x;
+}
+
+template <int DTYPE, bool TAIL>
+__global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
+    const PtrTable g_tab, uint64_t d, uint64_t bucket_elems, uint32_t slices, uint64_t slice_elems,
+    float g_min, char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes,
+    const MutPtrTable stats_tab)
+{
+    // blockIdx.y = tensor of the batch; each tensor has its own region of the workspace
+    const void* __restrict__ g = g_tab.p[blockIdx.y];
+    char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
+    uint32_t* __restrict__ ws_hist = reinterpret_cast<uint32_t*>(my_ws);
+    StatsExtra* __restrict__ ws_extra = reinterpret_cast<StatsExtra*>(my_ws + ws_hist_bytes);
+    const uint32_t blk = linear_block();
+    if ((uint64_t)(blk / slices) * bucket_elems >= d) return;          // padding of a folded grid
+    __shared__ StatsLds L;
+
+    const uint32_t bucket = blk / slices;
+    const uint32_t slice = blk - bucket * slices;
+    const uint64_t bstart = (uint64_t)bucket * bucket_elems;
+    const uint64_t bend = bstart + bucket_elems < d ? bstart + bucket_elems : d;
+    uint64_t cstart = bstart + (uint64_t)slice * slice_elems;
+    cstart = cstart < bend ? cstart : bend;
+    const uint64_t cend = cstart + slice_elems < bend ? cstart + slice_elems : bend;
+
+    // partial counts of this slice as one contiguous row of the workspace; a bucket that is one
+    // slice writes its record directly and no second kernel follows
+    const bool final_record = slices == 1u;
+    tq_stats_t* S = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]) + bucket;
+    uint32_t* row = final_record ? S->hist : ws_hist + ((uint64_t)bucket * slices + slice) * TQ_NBINS;
+    const StatsExtra x = stats_slice<DTYPE, TAIL>(g, cstart, cend, g_min, L, row);
+    if (threadIdx.x == 0) {
         if (final_record) write_scalars(S, x, bend - bstart, g_min);
         else ws_extra[(uint64_t)bucket * slices + slice] = x;
     }
@@ -344,6 +364,82 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
             const StatsExtra x{amax, nonfinite, n_tail, exp_sum, log2m_fix};
             write_scalars(S, x, hi - lo, g_min);
         }
+    }
+}
+
+
+// ---- variable-size segments (Sec. V: the layers of a network are quantized independently) ----
+//
+// The tensor is cut at seg_off[0] = 0 < ... < seg_off[nseg] = d (interior offsets multiples of
+// 128) and there is one record per segment.  Work is cut independently of the segments, into
+// chunks of kSegChunk elements, one workgroup each, so that the launch depends on d alone: a
+// workgroup takes the pieces of the segments that overlap its chunk one after the other and
+// writes one partial row per piece.  Pieces follow each other along the tensor, and from one
+// piece to the next either the chunk or the segment (or both) advances, so chunk + segment is
+// a unique row number below n_chunks + nseg.  A second kernel adds each segment's rows.
+
+constexpr uint64_t kSegChunk = 1ull << 17;             // elements per workgroup (32 tiles of 4096)
+
+template <int DTYPE, bool TAIL>
+__global__ __launch_bounds__(kStatsBlock) void tq_stats_segments_partial_kernel(
+    const void* __restrict__ g, uint64_t d, const uint64_t* __restrict__ seg_off, uint32_t nseg, float g_min,
+    uint32_t* __restrict__ ws_hist, StatsExtra* __restrict__ ws_extra)
+{
+    const uint32_t chunk = linear_block();
+    const uint64_t cstart = (uint64_t)chunk * kSegChunk;
+    if (cstart >= d) return;                                           // padding of a folded grid
+    const uint64_t cend = cstart + kSegChunk < d ? cstart + kSegChunk : d;
+    __shared__ StatsLds L;
+    uint32_t s = find_segment(seg_off, nseg, cstart);
+    for (;;) {
+        // the last segment ends at d whatever the table says: the loop ends with the chunk
+        uint64_t seg_lo = seg_off[s], seg_hi = s + 1 < nseg ? seg_off[s + 1] : d;
+        seg_lo = seg_lo > cstart ? (seg_lo < cend ? seg_lo : cend) : cstart;
+        seg_hi = seg_hi < cend ? (seg_hi > seg_lo ? seg_hi : seg_lo) : cend;
+        seg_lo &= ~7ull;                                               // groups of 8 never straddle a segment
+        const uint64_t r = (uint64_t)chunk + s;
+        const StatsExtra x = stats_slice<DTYPE, TAIL>(g, seg_lo, seg_hi, g_min, L, ws_hist + r * TQ_NBINS);
+        if (threadIdx.x == 0) ws_extra[r] = x;
+        if (seg_hi >= cend || s + 1 >= nseg) break;
+        ++s;
+        __syncthreads();                                               // the histograms are cleared again
+    }
+}
+
+// One workgroup per segment adds the rows of the chunks the segment overlaps.
+__global__ __launch_bounds__(kStatsBlock) void tq_stats_segments_reduce_kernel(
+    uint64_t d, const uint64_t* __restrict__ seg_off, uint32_t nseg, float g_min,
+    const uint32_t* __restrict__ ws_hist, const StatsExtra* __restrict__ ws_extra, uint64_t n_rows,
+    tq_stats_t* __restrict__ stats)
+{
+    const uint32_t s = linear_block();
+    if (s >= nseg) return;
+    const uint64_t lo = seg_off[s] < d ? seg_off[s] : d;
+    uint64_t hi = s + 1 < nseg ? seg_off[s + 1] : d;
+    hi = hi < d ? hi : d;
+    tq_stats_t* S = stats + s;
+    uint64_t r0 = lo / kSegChunk + s, r1 = hi > lo ? (hi - 1) / kSegChunk + s : r0;   // first and last row
+    r1 = r1 < n_rows ? r1 : n_rows - 1;
+    r0 = r0 < r1 ? r0 : r1;
+    const bool empty = hi <= lo;                                       // only with a malformed table
+    for (int b = threadIdx.x; b < TQ_NBINS; b += kStatsBlock) {
+        uint32_t total = 0u;
+        if (!empty)
+            for (uint64_t r = r0; r <= r1; ++r) total += ws_hist[r * TQ_NBINS + b];
+        S->hist[b] = total;
+    }
+    if (threadIdx.x == 0) {
+        StatsExtra x{0u, 0u, 0ull, 0ll, 0ull};
+        if (!empty)
+            for (uint64_t r = r0; r <= r1; ++r) {
+                const StatsExtra y = ws_extra[r];
+                x.absmax_bits = y.absmax_bits > x.absmax_bits ? y.absmax_bits : x.absmax_bits;
+                x.n_nonfinite += y.n_nonfinite;
+                x.n_tail += y.n_tail;
+                x.exp_sum += y.exp_sum;
+                x.log2m_fix += y.log2m_fix;
+            }
+        write_scalars(S, x, empty ? 0 : hi - lo, g_min);
     }
 }
 
@@ -463,5 +559,41 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
     if (!tq::fold_grid(rblocks, tq::kReduceBlock, (unsigned)count, rgrid)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(tq::tq_stats_reduce_kernel, rgrid, dim3(tq::kReduceBlock), 0,
                        st, ws, tensor_bytes, hist_bytes, p.slices, gpb, d, p.be, g_min, stt);
+    return hipGetLastError();
+}
+
+
+uint64_t tq_stats_segments_workspace_bytes_impl(uint64_t d, uint64_t nseg)
+{
+    if (d == 0 || nseg == 0) return 0;
+    const uint64_t rows = (d + tq::kSegChunk - 1) / tq::kSegChunk + nseg;
+    return (rows * (TQ_NBINS * 4 + sizeof(tq::StatsExtra)) + 255) / 256 * 256;
+}
+
+// Host side of tq_stats_segments after the argument checks of the C entry point.
+hipError_t tq_launch_stats_segments(const void* g, int dtype, uint64_t d, const uint64_t* seg_off, uint64_t nseg,
+                                    float g_min, tq_stats_t* stats, void* workspace, hipStream_t st)
+{
+    const uint64_t n_chunks = (d + tq::kSegChunk - 1) / tq::kSegChunk;
+    const uint64_t rows = n_chunks + nseg;
+    uint32_t* ws_hist = static_cast<uint32_t*>(workspace);
+    tq::StatsExtra* ws_extra = reinterpret_cast<tq::StatsExtra*>(static_cast<char*>(workspace) + rows * TQ_NBINS * 4);
+    dim3 pgrid, rgrid;
+    if (nseg > 0xFFFFFFFFull || !tq::fold_grid(n_chunks, tq::kStatsBlock, 1, pgrid) ||
+        !tq::fold_grid(nseg, tq::kStatsBlock, 1, rgrid))
+        return hipErrorInvalidValue;
+#define TQ_LAUNCH_SEG_PARTIAL(DT, TL)                                                                          \
+    hipLaunchKernelGGL((tq::tq_stats_segments_partial_kernel<DT, TL>), pgrid, dim3(tq::kStatsBlock), 0, st, g, d, \
+                       seg_off, (uint32_t)nseg, g_min, ws_hist, ws_extra)
+    if (dtype == TQ_F32) {
+        if (g_min > 0.0f) TQ_LAUNCH_SEG_PARTIAL(TQ_F32, true); else TQ_LAUNCH_SEG_PARTIAL(TQ_F32, false);
+    } else {
+        if (g_min > 0.0f) TQ_LAUNCH_SEG_PARTIAL(TQ_BF16, true); else TQ_LAUNCH_SEG_PARTIAL(TQ_BF16, false);
+    }
+#undef TQ_LAUNCH_SEG_PARTIAL
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(tq::tq_stats_segments_reduce_kernel, rgrid, dim3(tq::kStatsBlock), 0, st, d, seg_off,
+                       (uint32_t)nseg, g_min, ws_hist, ws_extra, rows, stats);
     return hipGetLastError();
 }

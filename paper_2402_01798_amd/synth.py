@@ -106,6 +106,24 @@ def _layer_scales(wl: Workload, worker: int, d: int) -> torch.Tensor:
     return scales
 
 
+def layer_segments(wl: Workload, d: Optional[int] = None):
+    """Offsets [0, ..., d] of the workload's layers (the same draw as ``_layer_scales``), each interior
+    boundary moved down to a multiple of 128: the segment table of a per-layer quantizer."""
+    d = wl.d if d is None else d
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(_seed(wl, 0, salt=1))
+    offs, pos = [0], 0
+    while pos < d:
+        length = int(2.0 ** (10.0 + 14.0 * torch.rand((), generator=gen).item()))
+        torch.rand((), generator=gen)                       # the layer's scale, drawn by _layer_scales
+        pos += length
+        cut = min(pos, d) // 128 * 128
+        if pos < d and cut > offs[-1]:
+            offs.append(cut)
+    offs.append(d)
+    return offs
+
+
 def as_numpy(t: torch.Tensor):
     """Host numpy view: float32 as is, bfloat16 as its uint16 bit patterns."""
     t = t.detach().cpu().contiguous()

@@ -61,7 +61,8 @@ def check_full(name, bits, grid, say, params_workers=2):
         assert np.allclose(S_dev["sum_log_tail"], S_or["sum_log_tail"], rtol=1e-6, atol=0)
         Pd = B.params_to_numpy(params[i]).view(O.PARAMS_DTYPE)
         if i < params_workers:
-            P_or = OP.tq_params(S_or, bits, grid)
+            P_or = OP.tq_params(S_dev, bits, grid)      # from the device's statistics bytes: the log-sum
+                                                        # agrees to 1e-6 only, and alpha amplifies that
             assert np.allclose(Pd["alpha"], P_or["alpha"], rtol=1e-6)
             assert np.allclose(Pd["level"], P_or["level"], rtol=1e-6, atol=0)
             assert (Pd["flags"] == P_or["flags"]).all() and (Pd["grid"] == grid).all()
