@@ -39,9 +39,10 @@ ALU_PEAK_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # (workload, bits, grid) of every variant the benchmark plan names; the first is the headline
 VARIANTS = [("cfg4", 2, 0), ("cfg4", 2, 1), ("cfg2", 2, 0), ("cfg2", 4, 0), ("cfg3", 3, 1), ("cfg5", 2, 1)]
 
-# vector-ALU instructions per element of the compress kernel's variants (counted in the
-# compiled code): only used to say which ceiling binds
-COMPRESS_VALU_PER_ELEM = {}
+# vector-ALU lane-operations per element of the compress kernel's variants, as rocprofv3's
+# SQ_INSTS_VALU counts them (profiles/valu_instructions.txt): they decide which ceiling binds
+COMPRESS_VALU_PER_ELEM = {"f32/b2/g0": 15.5, "f32/b2/g1": 20.2, "f32/b4/g0": 20.2, "f32/b3/g1": 29.4,
+                          "bf16/b2/g1": 20.5}
 
 
 def parse():
@@ -339,7 +340,10 @@ def compress_roofline(path, res):
             tlops = N * path.d * valu / (comp_us * 1e-6) / 1e12
             roof.update({"bound": "alu", "achieved": round(tlops, 2), "peak": round(ALU_PEAK_TLOPS, 1),
                          "unit": "T lane-op/s", "frac": round(tlops / ALU_PEAK_TLOPS, 4),
-                         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4)})
+                         "hbm_frac": round(gbps / HBM_PEAK_GBPS, 4),
+                         "note": "peak = one vector instruction per SIMD and cycle; this part overlaps "
+                                 "instructions of different kinds (a mixed probe issues 41.3 T/s), so a "
+                                 "kernel with no idle issue slot can read slightly above 1"})
     return roof
 
 
