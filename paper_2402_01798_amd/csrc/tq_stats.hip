@@ -36,7 +36,8 @@ constexpr int kStatsReplicas = 8;
 constexpr int kStatsStride = 929;                      // >= TQ_NBINS and = 1 mod 32: replicas in different banks
 constexpr int kStatsMinSlice = 4 * kStatsTile;         // smallest slice worth a workgroup (16384 elements)
 constexpr int kStatsMaxSlices = 256;                   // slices per bucket at most
-constexpr int kStatsTargetGroups = 256;                // workgroups aimed at in one launch (one per CU)
+constexpr int kStatsTargetGroups = 256;                // workgroups per tensor the workspace is sized for (one per CU)
+constexpr int kStatsResidentGroups = 1024;             // workgroups that can run at the same time (4 per CU)
 constexpr int kReduceBlock = 1024;                     // threads of the reduce kernel: 64 bins x 16 slice lanes
 constexpr int kReduceBins = 64;
 constexpr int kBinBias = 1391;                         // 16 * (biased exponent of 2^-40) - 1
@@ -464,13 +465,16 @@ uint32_t max_slices(uint64_t be, uint64_t nb)
     return (uint32_t)(m < 1 ? 1 : m);
 }
 
-// Slices per bucket for a batch of `count` tensors.  Measured on MI355X: the partial kernel is
-// fastest with about one 512-thread workgroup per compute unit in the whole launch (each
-// workgroup pays for clearing and flushing its LDS histograms -- about what reading 16384
-// elements costs -- so fewer, longer-lived workgroups win as long as every CU has one), and a
-// launch of W workgroups takes ceil(W / 256) times one workgroup's time: 357 workgroups are as
-// slow as 512.  The slice count minimises that product.
-StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems, int count)
+// Slices per bucket for a batch of `count` tensors.  Each workgroup pays for clearing and
+// flushing its LDS histograms -- about what reading 16384 elements costs -- so fewer, longer-lived
+// workgroups win as long as the machine is full, and a launch of W workgroups takes
+// ceil(W / resident) times one workgroup's time, `resident` being the workgroups the launch
+// should keep running at the same time.  The slice count minimises that product.  Measured on
+// MI355X: the fp32 kernels are bound by memory and are fastest with one workgroup per CU
+// (8 x 11.2 M: 71 us against 76 with four); the bf16 kernel is bound by instruction issue and
+// needs the four a CU can hold (4 x 10^9 bf16 with tail terms: 1850 us with 256 workgroups,
+// 1520 with 1024).
+StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems, int count, uint64_t resident)
 {
     StatsPlan p;
     p.be = bucket_elems ? bucket_elems : d;
@@ -480,7 +484,7 @@ StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems, int count)
     uint32_t best = 1;
     uint64_t best_cost = ~0ull;
     for (uint32_t sl = 1; sl <= smax; ++sl) {
-        const uint64_t rounds = (units * sl + tq::kStatsTargetGroups - 1) / tq::kStatsTargetGroups;
+        const uint64_t rounds = (units * sl + resident - 1) / resident;
         const uint64_t cost = rounds * ((p.be + sl - 1) / sl + (uint64_t)tq::kStatsMinSlice);
         if (cost < best_cost) { best_cost = cost; best = sl; }
     }
@@ -530,7 +534,9 @@ hipError_t tq_stats_static_scratch(void** out)
 hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
                            float g_min, tq_stats_t* const* stats, void* workspace, hipStream_t st)
 {
-    const StatsPlan p = plan_stats(d, bucket_elems, count);
+    // bf16 elements cost half the bytes but all the instructions: that kernel is bound by issue and
+    // wants every wavefront slot, the fp32 ones are bound by memory and want the fewest flushes
+    const StatsPlan p = plan_stats(d, bucket_elems, count, dtype == TQ_BF16 ? tq::kStatsResidentGroups : tq::kStatsTargetGroups);
     const uint64_t nblocks = p.nb * p.slices;
     dim3 pgrid;
     if (count < 1 || count > tq::kMaxBatch || !tq::fold_grid(nblocks, tq::kStatsBlock, (unsigned)count, pgrid))
