@@ -373,13 +373,13 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
 //
 // The tensor is cut at seg_off[0] = 0 < ... < seg_off[nseg] = d (interior offsets multiples of
 // 128) and there is one record per segment.  Work is cut independently of the segments, into
-// chunks of kSegChunk elements, one workgroup each, so that the launch depends on d alone: a
+// chunks of kSegChunk (2^19) elements, one workgroup each, so that the launch depends on d alone: a
 // workgroup takes the pieces of the segments that overlap its chunk one after the other and
 // writes one partial row per piece.  Pieces follow each other along the tensor, and from one
 // piece to the next either the chunk or the segment (or both) advances, so chunk + segment is
 // a unique row number below n_chunks + nseg.  A second kernel adds each segment's rows.
 
-constexpr uint64_t kSegChunk = 1ull << 17;             // elements per workgroup (32 tiles of 4096)
+constexpr uint64_t kSegChunk = 1ull << 19;             // elements per workgroup (128 tiles of 4096)
 
 template <int DTYPE, bool TAIL>
 __global__ __launch_bounds__(kStatsBlock) void tq_stats_segments_partial_kernel(
