@@ -83,14 +83,6 @@ __device__ __forceinline__ void replace_nan(float (&x)[8])
 // Any codebook: cell k by comparison with the levels, p_r = (x - l_k) * inv_w[k] (two
 // roundings), the upper end iff u = 1 - (rf + 1/2) / 2^16 <= p_r.  The uniform codebook: the
 // same rounding stated through the position in units of cells, floor(t + U), U = (rf + 1/2) / 2^16.
-//
-// The truncation of Eq. (1) is written out only where it changes something.  On the level-table
-// path it changes nothing: beyond +alpha the cell is still the last one and p_r only grows past
-// 1 (or stays 0 for an empty cell), so the upper end alpha is taken for every draw, which is
-// what T_alpha(x) = alpha gives; below -alpha the cell is the first one and p_r < 0, so the
-// lower end -alpha is taken for every draw; +-Inf go the same ways (Inf times a zero reciprocal
-// is NaN, and u <= NaN is false: the lower end, as for the truncated value).  Requires what
-// tq_params_t promises: level[s] = alpha, level[0] = -alpha, finite inv_w.
 // Uniform codebook: the code of one element.
 template <int BITS>
 __device__ __forceinline__ uint32_t quantize_uniform(float x, float rf, float alpha, float inv_step)
@@ -148,14 +140,23 @@ __device__ __forceinline__ uint32_t quantize(float x, float rf, float alpha, flo
     if constexpr (GRID == TQ_GRID_UNIFORM) {
         return quantize_uniform<BITS>(x, rf, alpha, inv_step);
     } else {
-        const uint32_t a = cell_offset<BITS>(x, lv, tab);
-        return (a >> 4) + (rounds_up(x, rf, a, tab) ? 1u : 0u);
+        const float xc = __builtin_amdgcn_fmed3f(x, -alpha, alpha);  // Eq. (1)
+        const uint32_t a = cell_offset<BITS>(xc, lv, tab);
+        return (a >> 4) + (rounds_up(xc, rf, a, tab) ? 1u : 0u);
     }
 }
 
 // Codes of one lane's 8 elements, packed little-endian into the low 8*BITS bits.
 // PARTIAL: only the first n_valid elements exist; the others encode as 0 (pad bits).
-template <int BITS, int GRID, bool PARTIAL>
+// CLAMP (level-table path): whether the truncation of Eq. (1) is written out.  It changes the
+// code only when the FIRST cell of the codebook is empty (l_1 = l_0 = -alpha, a degenerate
+// bucket): a value below -alpha is truncated onto that repeated level and then belongs to the
+// cell above it.  Otherwise it changes nothing -- below -alpha the cell is the first one and
+// p_r < 0, beyond +alpha it is the last one and p_r >= 1 (or 0 for an empty last cell), +-Inf
+// go the same ways (Inf times a zero reciprocal is NaN, and u <= NaN is false: the lower end,
+// as for the truncated value) -- so the caller leaves it out unless l_1 = l_0: one
+// instruction per element of a kernel that is bound by instruction issue.
+template <int BITS, int GRID, bool PARTIAL, bool CLAMP = true>
 __device__ __forceinline__ uint32_t encode_group(const float (&x)[8], const uint32_t (&rw)[4], int n_valid,
                                                  float alpha, float inv_step, const float (&lv)[16],
                                                  const LevelLds& tab)
@@ -177,8 +178,9 @@ __device__ __forceinline__ uint32_t encode_group(const float (&x)[8], const uint
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t r = (j & 1) ? (rw[j >> 1] >> 16) : (rw[j >> 1] & 0xFFFFu);
-            uint32_t a = cell_offset<BITS>(x[j], lv, tab);
-            bool up = rounds_up(x[j], (float)r, a, tab);
+            const float xc = CLAMP ? __builtin_amdgcn_fmed3f(x[j], -alpha, alpha) : x[j];   // Eq. (1); NaN is gone
+            uint32_t a = cell_offset<BITS>(xc, lv, tab);
+            bool up = rounds_up(xc, (float)r, a, tab);
             if (PARTIAL && j >= n_valid) { a = 0; up = false; }
             cells |= (j * BITS >= 4) ? a << (j * BITS - 4) : a >> (4 - j * BITS);
             ups |= up ? 1u << (j * BITS) : 0u;
@@ -248,10 +250,12 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     const float inv_step = P->inv_w[0];
     const bool nonuniform = P->grid != TQ_GRID_UNIFORM;        // uniform over the workgroup
     const uint32_t lane = threadIdx.x;                         // this thread's group within a tile
+    bool first_cell_empty = false;                             // see encode_group's CLAMP
     if (nonuniform) {
         fill_level_lds(tab, P, (1u << BITS) - 1u);
 #pragma unroll
         for (int j = 0; j < 16; ++j) lv[j] = P->level[j];       // wave-uniform: scalar loads
+        first_cell_empty = !(lv[1] > lv[0]);
         __syncthreads();
     }
 
@@ -280,9 +284,10 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             replace_nan(x[t]);
-            const uint32_t word =
-                nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x[t], rw[t], 8, alpha, inv_step, lv, tab)
-                           : encode_group<BITS, TQ_GRID_UNIFORM, false>(x[t], rw[t], 8, alpha, inv_step, lv, tab);
+            uint32_t word;
+            if (!nonuniform) word = encode_group<BITS, TQ_GRID_UNIFORM, false>(x[t], rw[t], 8, alpha, inv_step, lv, tab);
+            else if (first_cell_empty) word = encode_group<BITS, TQ_GRID_NONUNIFORM, false, true>(x[t], rw[t], 8, alpha, inv_step, lv, tab);
+            else word = encode_group<BITS, TQ_GRID_NONUNIFORM, false, false>(x[t], rw[t], 8, alpha, inv_step, lv, tab);
             store_codes<BITS>(payload + (((gbase + (uint64_t)t * kTile) >> 3) + lane) * (uint64_t)BITS, word);
         }
         return;

@@ -85,6 +85,41 @@ def test_hand_made_asymmetric_codebook():
     assert (got == O.compress(g_np, P2, 1, 1, 1)).all()
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("lv", [[-1.0, -1.0, 1.0, 1.0],                          # empty first and last cell
+                                [-1.0, -1.0, 0.0, 0.5, 0.5, 0.75, 1.0, 1.0],
+                                [-1.0, -1.0, -1.0, 0.25, 0.25, 0.5, 0.5, 1.0, 1.0, 1.0, 1.0, 1.0, 1.0, 1.0, 1.0, 1.0]])
+def test_empty_end_cells_and_values_beyond_the_threshold(lv, dtype):
+    """Degenerate buckets give codebooks whose first or last cells are empty (levels repeated at -alpha
+    or +alpha).  A value beyond -alpha is truncated ONTO the repeated level and so belongs to the cell
+    above it (code 1 or 2, not 0): the truncation of Eq. (1) has to happen before the cell is looked
+    up, also on the level-table path.  Values at, next to and far beyond +-alpha, infinities, NaN."""
+    lv = np.array(lv, dtype=np.float32)
+    s = lv.size - 1
+    bits = {3: 2, 7: 3, 15: 4}[s]
+    P = np.zeros(1, dtype=O.PARAMS_DTYPE)
+    P["alpha"], P["bits"], P["s"], P["grid"] = 1.0, bits, s, O.GRID_NONUNIFORM
+    P["level"][0, : s + 1] = lv
+    width = np.diff(lv.astype(np.float64))
+    P["inv_w"][0, :s] = np.where(width > 0, 1.0 / np.where(width > 0, width, 1.0), 0.0)
+    d = 3 * 2048 + 77
+    rng = np.random.default_rng(s)
+    g = rng.standard_normal(d).astype(np.float32)
+    special = np.array([1.0, -1.0, np.nextafter(np.float32(1), np.float32(2)), np.nextafter(np.float32(-1), np.float32(-2)),
+                        1.5, -1.5, 3e38, -3e38, np.inf, -np.inf, np.nan, 0.0, -0.0, 0.25, 0.5, 0.75], dtype=np.float32)
+    g[:: 97][: special.size] = special
+    g[-16:] = special
+    t = torch.from_numpy(g).to(dtype)
+    g_np = t.view(torch.int16).numpy().view("uint16") if dtype == torch.bfloat16 else t.numpy()
+    got = device_compress(t.cuda(), P, bits, 5, 1, 2).cpu().numpy()
+    want = O.compress(g_np, P, 5, 1, 2)
+    assert (got == want).all()
+    codes = np.unpackbits(want, bitorder="little")[: d * bits].reshape(d, bits)
+    codes = (codes.astype(np.uint32) << np.arange(bits, dtype=np.uint32)).sum(axis=1)
+    below = np.nonzero(g < -1.0)[0]
+    assert below.size > 0 and (codes[below] > 0).all()        # truncated onto the repeated level: the cell above
+
+
 @pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("d", [1, 5, 40, 41, 42, 43, 85, 86, 127, 128, 129, 2049, 4096 + 41])
 def test_nothing_is_written_past_the_payload(bits, d):

@@ -24,7 +24,9 @@ def make_params(levels, grid, alpha=None):
     if grid == O.GRID_UNIFORM:
         P["inv_w"][0, :s] = np.float32(s / (2.0 * float(P["alpha"][0])))
     else:
-        P["inv_w"][0, :s] = (1.0 / np.diff(levels.astype(np.float64))).astype(np.float32)
+        width = np.diff(levels.astype(np.float64))
+        # an empty cell has reciprocal 0, as the parameter record is specified
+        P["inv_w"][0, :s] = np.where(width > 0, 1.0 / np.where(width > 0, width, 1.0), 0.0).astype(np.float32)
     return P
 
 
@@ -191,3 +193,35 @@ def test_mean_over_steps_converges_to_the_truncated_gradient():
     width = 1.0 / 3
     sigma = width / 2 / np.sqrt(M)
     assert np.abs(mean - np.clip(g, -0.5, 0.5)).max() < 5 * sigma
+
+
+@pytest.mark.parametrize("P", [make_params(NONUNIFORM_7, O.GRID_NONUNIFORM),
+                               make_params(NONUNIFORM_3, O.GRID_NONUNIFORM),
+                               make_params([-0.05, -0.01, 0.02, 0.05], O.GRID_NONUNIFORM),
+                               make_params([-1.0, -0.5, 0.0, 0.5, 0.5, 0.75, 1.0, 1.0], O.GRID_NONUNIFORM),
+                               make_params([-1.0, -1.0 + 2.0 ** -23, 0.0, 1.0], O.GRID_NONUNIFORM)])
+def test_on_a_level_table_truncation_changes_the_code_only_through_an_empty_first_cell(P):
+    """Eq. (1) followed by Eq. (2) on a level table whose first cell is not empty: beyond +alpha the
+    cell is the last one and p_r is at least 1 (or 0 for an empty last cell), below -alpha it is the
+    first one and p_r is below 0, so the code is the end level for every draw whether or not the value
+    was truncated first.  (The GPU kernel's level-table path relies on this: it writes the
+    truncation out only for codebooks with l_1 = l_0.)  Checked by enumerating all draws with the
+    truncation switched off -- the same codebook under a threshold nothing exceeds."""
+    free = P.copy()
+    free["alpha"] = np.float32(3.4e38)
+    a = float(P["alpha"][0])
+    s = int(P["s"][0])
+    lv = P["level"][0, : s + 1]
+    assert lv[1] > lv[0]
+    xs = [a, np.nextafter(np.float32(a), np.float32(np.inf)), 1.5 * a, 100 * a, 3.0e38, np.inf,
+          -a, np.nextafter(np.float32(-a), np.float32(-np.inf)), -1.5 * a, -3.0e38, -np.inf]
+    xs += [float(l) for l in lv] + [0.0, 0.3 * a, -0.7 * a]
+    for x in xs:
+        with_t = O.enumerate_draws(np.float32(x), P, eq2=True)
+        without = O.enumerate_draws(np.float32(x), free, eq2=True)
+        assert (with_t == without).all(), (float(x), with_t[: s + 1], without[: s + 1])
+    # ... and the exception: an empty first cell, a value below -alpha
+    E = make_params([-1.0, -1.0, 0.0, 1.0], O.GRID_NONUNIFORM)
+    F = E.copy()
+    F["alpha"] = np.float32(3.4e38)
+    assert O.quantize_eq2(-2.0, E, 7) == 1 and O.quantize_eq2(-2.0, F, 7) == 0
