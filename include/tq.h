@@ -107,7 +107,7 @@ int tq_stats(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
  * allocates and frees nothing.  Arguments and result as tq_stats; g_dev and stats_dev are
  * still the caller's.
  *   - TQ_EUNSUPPORTED when tq_stats_workspace_bytes(d, bucket_elems) exceeds the scratch
- *     array (more than about 1100 buckets)
+ *     array (more than about 1200 buckets)
  *   - every call on a device shares that device's array: calls that may overlap in time
  *     on one device (different streams, no ordering between them) race and give wrong
  *     statistics; order them, or use tq_stats with separate workspaces.  Nothing has to
@@ -115,7 +115,7 @@ int tq_stats(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
  *   - the device of the call is the current device (hipSetDevice); the first call on a
  *     device looks the array's address up
  */
-#define TQ_STATS_STATIC_SCRATCH_BYTES (4u << 20)
+#define TQ_STATS_STATIC_SCRATCH_BYTES (8u << 20)
 int tq_stats_static(const void* g_dev, int dtype, uint64_t d, uint64_t bucket_elems,
                     float g_min, tq_stats_t* stats_dev, void* stream);
 

@@ -18,6 +18,7 @@
 // Counts are integers and the tail's log-sum travels as exact integer sums, so the result
 // depends neither on scheduling nor on how the tensor was sliced or batched.
 #include <atomic>
+#include <type_traits>
 
 #include "tq_device.h"
 
@@ -77,17 +78,31 @@ __device__ __forceinline__ uint32_t wave_reduce_max(uint32_t v)
     return v;
 }
 
+// One lane's group of 8 consecutive elements as it is loaded (32 bytes of fp32, 16 of bf16), and
+// as fp32 bit patterns.  The two are separate so that nothing that needs the loaded value stands
+// between a request and the work it is meant to overlap.
+template <int DTYPE> struct RawGroup { uint4 q[DTYPE == TQ_F32 ? 2 : 1]; };
+
 template <int DTYPE>
-__device__ __forceinline__ void load_bits(const void* g, uint64_t e0, uint32_t (&bits)[8])
+__device__ __forceinline__ void load_raw(const void* g, uint64_t e0, RawGroup<DTYPE>& r)
 {
     if constexpr (DTYPE == TQ_F32) {
         const uint4* p = reinterpret_cast<const uint4*>(static_cast<const float*>(g) + e0);
-        const uint4 a = p[0], b = p[1];
-        bits[0] = a.x; bits[1] = a.y; bits[2] = a.z; bits[3] = a.w;
-        bits[4] = b.x; bits[5] = b.y; bits[6] = b.z; bits[7] = b.w;
+        r.q[0] = p[0];
+        r.q[1] = p[1];
     } else {
-        const uint4 v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(g) + e0);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        r.q[0] = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(g) + e0);
+    }
+}
+
+template <int DTYPE>
+__device__ __forceinline__ void raw_bits(const RawGroup<DTYPE>& r, uint32_t (&bits)[8])
+{
+    if constexpr (DTYPE == TQ_F32) {
+        bits[0] = r.q[0].x; bits[1] = r.q[0].y; bits[2] = r.q[0].z; bits[3] = r.q[0].w;
+        bits[4] = r.q[1].x; bits[5] = r.q[1].y; bits[6] = r.q[1].z; bits[7] = r.q[1].w;
+    } else {
+        const uint32_t w[4] = {r.q[0].x, r.q[0].y, r.q[0].z, r.q[0].w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) { bits[2 * i] = w[i] << 16; bits[2 * i + 1] = w[i] & 0xFFFF0000u; }
     }
@@ -124,13 +139,60 @@ template <int DTYPE, bool TAIL>
 __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, uint64_t cstart, uint64_t cend,
                                                   float g_min, StatsLds& L, uint32_t* __restrict__ row)
 {
+    // Full trips of kTrip tiles each, two register buffers: the next trip's 16-byte loads are
+    // requested before the current trip's values are histogrammed.  The trip count is the same
+    // for every lane of the workgroup; what is left after the full trips is less than a trip.
+    //  - bf16 is bound by instruction issue: trips of two tiles, and the wavefront works on one
+    //    buffer while the other one's loads are in flight.
+    //  - fp32 is bound by memory and runs with two wavefronts per SIMD: trips of four tiles
+    //    (eight 16-byte loads per lane), and the wavefront waits for ALL its loads, the ones
+    //    just requested included, before it works on the older buffer -- so it has nothing in
+    //    flight while it computes, and the other wavefront of the SIMD fills the gap.  Measured
+    //    on 8 x 124 M fp32: 705 us when a wavefront keeps loads in flight under its own work,
+    //    677-682 us this way (698 with trips of two tiles, 697 with six, 709 with eight); the
+    //    memory system gives more with fewer requests outstanding per compute unit, as it
+    //    does for a plain read loop once arithmetic is added to it.
+    constexpr int kTrip = DTYPE == TQ_F32 ? 4 : 2;
+    constexpr bool kWaitAll = DTYPE == TQ_F32;
+    const uint64_t lane_e = cstart + (uint64_t)threadIdx.x * kGroup;
+    const uint32_t n_trips = (uint32_t)((cend - cstart) / ((uint64_t)kTrip * kStatsTile));
+    // Two register buffers that swap roles (no copies: a copy would wait for the loads in
+    // flight); sched_barrier keeps each request ahead of the work it overlaps.  The requests
+    // of the loop are unconditional: a branch between a request and the work after it would
+    // make the compiler wait for every load in flight where the paths join.  What is left
+    // after the full trips is at most kTrip tiles; there a lane requests the whole groups it has.
+    RawGroup<DTYPE> bufA[kTrip], bufB[kTrip];
+    const uint64_t rest = lane_e + (uint64_t)n_trips * kTrip * kStatsTile;
+    auto request = [&](RawGroup<DTYPE> (&buf)[kTrip], uint32_t trip) {
+#pragma unroll
+        for (int t = 0; t < kTrip; ++t)
+            load_raw<DTYPE>(g, lane_e + ((uint64_t)trip * kTrip + t) * kStatsTile, buf[t]);
+    };
+    auto request_rest = [&](RawGroup<DTYPE> (&buf)[kTrip]) {
+#pragma unroll
+        for (int t = 0; t < kTrip; ++t) {
+            const uint64_t e0 = rest + (uint64_t)t * kStatsTile;
+            if (e0 + kGroup <= cend) load_raw<DTYPE>(g, e0, buf[t]);
+        }
+    };
+    // on its way while the histograms are cleared
+    if (n_trips > 0) request(bufA, 0); else request_rest(bufA);
+    __builtin_amdgcn_sched_barrier(0);
+
     uint32_t* hist = L.hist;
     for (int i = threadIdx.x; i < kStatsReplicas * kStatsStride; i += kStatsBlock) hist[i] = 0u;
     __syncthreads();
 
     uint32_t* my_hist = hist + (threadIdx.x & (kStatsReplicas - 1)) * kStatsStride;
+    // LDS byte address of the lane's replica, less the bias of the bin index, as one opaque
+    // register: the address of a bin is then one shift-and-add on the clamped magnitude bits
+    using lds_u32 = __attribute__((address_space(3))) uint32_t;
+    uint32_t biased_base = (uint32_t)(uintptr_t)(lds_u32*)my_hist - 4u * (uint32_t)kBinBias;
+    asm volatile("" : "+v"(biased_base));
     const uint32_t gmin_bits = __float_as_uint(g_min);
-    uint32_t amax_bits = 0u, nonfinite = 0u, n_tail = 0u;
+    uint32_t amax_bits = 0u, nonfinite = 0u;
+    uint32_t n_tail_wave = 0u;           // tail elements the whole wavefront has seen in the full trips (same in every lane)
+    uint32_t n_tail_lane = 0u;           // tail elements this lane has seen where only part of the wavefront runs
     uint32_t not_counted = 0u;           // values this lane put into bin 0 that do not belong there
     uint32_t exp_acc = 0u;               // sum of BIASED exponents of the tail elements
     unsigned long long log2m_fix = 0ull; // sum of log2(product of 8 mantissas in [1,2)) in 2^-28 fixed point
@@ -141,7 +203,10 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
     // they counted and replaced by 0 -- which lands in bin 0 and is taken out of it again
     // before the counts are written.  The tail's log-sum costs one logarithm per group: the
     // eight mantissas (1.0 for a value outside the tail) are multiplied in a fixed tree order.
-    auto take_group = [&](const uint32_t (&raw)[8]) {
+    // ALL_LANES: called with the whole wavefront active; the tail count is then taken by the scalar
+    // unit from the compare masks, which saves a vector instruction per element.
+    auto take_group = [&](const uint32_t (&raw)[8], auto all_lanes) {
+        constexpr bool ALL_LANES = decltype(all_lanes)::value;
         uint32_t a[8];                                                 // |g| as ordered integers
 #pragma unroll
         for (int j = 0; j < 8; ++j) a[j] = raw[j] & 0x7FFFFFFFu;
@@ -164,16 +229,17 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
         amax_bits = m > amax_bits ? m : amax_bits;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            int32_t idx = (int32_t)(a[j] >> 19) - kBinBias;
-            idx = idx < 0 ? 0 : (idx > TQ_NBINS - 1 ? TQ_NBINS - 1 : idx);
-            atomicAdd(&my_hist[idx], 1u);
+            uint32_t c = a[j] >> 19;                                   // bin = 16 per octave, counted from 2^-40
+            c = c < (uint32_t)kBinBias ? (uint32_t)kBinBias : (c > (uint32_t)(kBinBias + TQ_NBINS - 1) ? (uint32_t)(kBinBias + TQ_NBINS - 1) : c);
+            __hip_atomic_fetch_add((lds_u32*)(uintptr_t)(biased_base + (c << 2)), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         if constexpr (TAIL) {                                          // g_min >= 2^-40: a tail value is normal
             float mant[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const bool in_tail = a[j] > gmin_bits;
-                n_tail += in_tail ? 1u : 0u;
+                if constexpr (ALL_LANES) n_tail_wave += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(in_tail));
+                else n_tail_lane += in_tail ? 1u : 0u;
                 const uint32_t am = in_tail ? a[j] : 0u;              // exponent 0, mantissa 1.0 outside the tail
                 exp_acc += am >> 23;
                 mant[j] = __uint_as_float((am & 0x007FFFFFu) | 0x3F800000u);
@@ -183,59 +249,72 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
         }
     };
 
-    // Full trips of two tiles each, software-pipelined: the next trip's four 16-byte loads per
-    // lane are requested before the current trip's 16 values are histogrammed.  The trip count
-    // is the same for every lane of the workgroup; the rest of the slice follows tile by tile.
-    constexpr int kTrip = 2;
-    const uint64_t lane_e = cstart + (uint64_t)threadIdx.x * kGroup;
-    const uint32_t n_trips = (uint32_t)((cend - cstart) / ((uint64_t)kTrip * kStatsTile));
-    if (n_trips > 0) {
-        // two register buffers that swap roles (no copies: a copy would wait for the loads in
-        // flight); sched_barrier keeps each request ahead of the histogramming it overlaps
-        uint32_t bufA[kTrip][8], bufB[kTrip][8];
-        auto request = [&](uint32_t (&buf)[kTrip][8], uint32_t trip) {
-            trip = trip < n_trips ? trip : n_trips - 1;               // past the end: re-request the last trip
+    auto consume = [&](const RawGroup<DTYPE> (&buf)[kTrip]) {
 #pragma unroll
-            for (int t = 0; t < kTrip; ++t)
-                load_bits<DTYPE>(g, lane_e + ((uint64_t)trip * kTrip + t) * kStatsTile, buf[t]);
-        };
-        auto consume = [&](const uint32_t (&buf)[kTrip][8]) {
-#pragma unroll
-            for (int t = 0; t < kTrip; ++t) take_group(buf[t]);
-        };
-        request(bufA, 0);
-        const uint32_t pairs = n_trips >> 1;
-        for (uint32_t p = 0; p < pairs; ++p) {
-            request(bufB, 2 * p + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            consume(bufA);
-            __builtin_amdgcn_sched_barrier(0);
-            request(bufA, 2 * p + 2);
-            __builtin_amdgcn_sched_barrier(0);
-            consume(bufB);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < kTrip; ++t) {
+            uint32_t bits[8];
+            raw_bits<DTYPE>(buf[t], bits);
+            take_group(bits, std::true_type{});
         }
-        if (n_trips & 1u) consume(bufA);                               // holds trip n_trips - 1
-    }
-    for (uint64_t e0 = lane_e + (uint64_t)n_trips * kTrip * kStatsTile; e0 < cend; e0 += kStatsTile) {
-        if (e0 + kGroup <= cend) {
-            uint32_t b0[8];
-            load_bits<DTYPE>(g, e0, b0);
-            take_group(b0);
-        } else {                                                       // ragged end of the tensor
-            const int n_valid = (int)(cend - e0);                      // the absent values enter as 0
-            uint32_t b0[8];
+    };
+    // what is left after the full trips: whole groups from the buffer, the one group that the
+    // end of the range cuts value by value
+    auto consume_rest = [&](const RawGroup<DTYPE> (&buf)[kTrip]) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                b0[j] = 0u;
-                if (j < n_valid) {
-                    if constexpr (DTYPE == TQ_F32) b0[j] = static_cast<const uint32_t*>(g)[e0 + j];
-                    else b0[j] = (uint32_t) static_cast<const uint16_t*>(g)[e0 + j] << 16;
+        for (int t = 0; t < kTrip; ++t) {
+            const uint64_t e0 = rest + (uint64_t)t * kStatsTile;
+            if (e0 + kGroup <= cend) {
+                uint32_t bits[8];
+                raw_bits<DTYPE>(buf[t], bits);
+                take_group(bits, std::false_type{});
+            } else if (e0 < cend) {                                    // ragged end of the range
+                const int n_valid = (int)(cend - e0);                  // the absent values enter as 0
+                uint32_t b0[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    b0[j] = 0u;
+                    if (j < n_valid) {
+                        if constexpr (DTYPE == TQ_F32) b0[j] = static_cast<const uint32_t*>(g)[e0 + j];
+                        else b0[j] = (uint32_t) static_cast<const uint16_t*>(g)[e0 + j] << 16;
+                    }
                 }
+                take_group(b0, std::false_type{});
+                not_counted += (uint32_t)(8 - n_valid);
             }
-            take_group(b0);
-            not_counted += (uint32_t)(8 - n_valid);
         }
+    };
+    // bufA holds trip 2p; the loop ends with the last or the last but one full trip in bufA
+    const uint32_t loops = n_trips > 0 ? (n_trips - 1) >> 1 : 0;
+    for (uint32_t p = 0; p < loops; ++p) {
+        request(bufB, 2 * p + 1);
+        if constexpr (kWaitAll) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        consume(bufA);
+        __builtin_amdgcn_sched_barrier(0);
+        request(bufA, 2 * p + 2);
+        if constexpr (kWaitAll) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        consume(bufB);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (n_trips == 0) {                                                // bufA holds the rest
+        consume_rest(bufA);
+    } else if (n_trips & 1u) {                                         // bufA holds the last full trip
+        request_rest(bufB);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(bufA);
+        __builtin_amdgcn_sched_barrier(0);
+        consume_rest(bufB);
+    } else {                                                           // bufA holds the last but one
+        request(bufB, n_trips - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(bufA);
+        __builtin_amdgcn_sched_barrier(0);
+        request_rest(bufA);
+        __builtin_amdgcn_sched_barrier(0);
+        consume(bufB);
+        __builtin_amdgcn_sched_barrier(0);
+        consume_rest(bufA);
     }
     // NaN, Inf and the absent values of a ragged group were counted as zeros: take them out again
     not_counted += nonfinite;
@@ -254,7 +333,7 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     amax_bits = wave_reduce_max(amax_bits);
     nonfinite = wave_reduce_add(nonfinite);
-    const unsigned long long nt = wave_reduce_add((unsigned long long)n_tail);
+    const unsigned long long nt = wave_reduce_add((unsigned long long)n_tail_lane) + n_tail_wave;
     const unsigned long long es = wave_reduce_add((unsigned long long)exp_acc);
     const unsigned long long lf = wave_reduce_add(log2m_fix);
     if (lane == 0) { L.red_u32[0][wave] = amax_bits; L.red_u32[1][wave] = nonfinite; L.red_u64[0][wave] = nt; L.red_u64[1][wave] = es; L.red_u64[2][wave] = lf; }
@@ -308,29 +387,21 @@ __global__ __launch_bounds__(kStatsBlock) void tq_stats_partial_kernel(
     }
 }
 
-__global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
-    const char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes, uint32_t slices,
-    uint32_t groups_per_bucket, uint64_t d, uint64_t bucket_elems, float g_min, const MutPtrTable stats_tab)
+// Adds `rows` consecutive partial rows (row0 onwards) of one bucket into its record S.  The
+// bucket's workgroups are numbered grp = 0 .. groups_per_bucket - 1: all but the last take 64
+// bins each, the last one the scalar fields.  n = elements of the bucket.
+__device__ __forceinline__ void reduce_rows(const uint32_t* __restrict__ ws_hist, const StatsExtra* __restrict__ ws_extra,
+                                            uint64_t row0, uint32_t rows, uint32_t grp, uint32_t groups_per_bucket,
+                                            tq_stats_t* __restrict__ S, uint64_t n, float g_min, uint32_t* part)
 {
-    __shared__ uint32_t part[kReduceBlock];
-    const char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
-    const uint32_t* __restrict__ ws_hist = reinterpret_cast<const uint32_t*>(my_ws);
-    const StatsExtra* __restrict__ ws_extra = reinterpret_cast<const StatsExtra*>(my_ws + ws_hist_bytes);
-    tq_stats_t* __restrict__ stats = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]);
-    const uint32_t blk = linear_block();
-    const uint32_t bucket = blk / groups_per_bucket;
-    const uint32_t grp = blk - bucket * groups_per_bucket;
-    if ((uint64_t)bucket * bucket_elems >= d) return;                  // padding of a folded grid
-    tq_stats_t* S = stats + bucket;
-
     if (grp + 1 < groups_per_bucket) {
-        // 64 consecutive bins x 16 interleaved slice lanes; a wavefront reads 256 contiguous bytes
+        // 64 consecutive bins x 16 interleaved row lanes; a wavefront reads 256 contiguous bytes
         const uint32_t bin = grp * kReduceBins + (threadIdx.x & (kReduceBins - 1));
         const uint32_t sl = threadIdx.x / kReduceBins;
         uint32_t total = 0u;
         if (bin < TQ_NBINS) {
-            const uint32_t* col = ws_hist + (uint64_t)bucket * slices * TQ_NBINS + bin;
-            for (uint32_t p = sl; p < slices; p += kReduceBlock / kReduceBins) total += col[(uint64_t)p * TQ_NBINS];
+            const uint32_t* col = ws_hist + row0 * TQ_NBINS + bin;
+            for (uint32_t p = sl; p < rows; p += kReduceBlock / kReduceBins) total += col[(uint64_t)p * TQ_NBINS];
         }
         part[threadIdx.x] = total;
         __syncthreads();
@@ -340,13 +411,13 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
             S->hist[bin] = total;
         }
     } else if (threadIdx.x < 64) {
-        // last workgroup of the bucket: max, counts and the log-sum of the slices (fixed order)
+        // last workgroup of the bucket: max, counts and the log-sum of the rows (integer sums)
         const int lane = threadIdx.x;
-        const StatsExtra* row = ws_extra + (uint64_t)bucket * slices;
+        const StatsExtra* row = ws_extra + row0;
         uint32_t amax = 0u, nonfinite = 0u;
         unsigned long long n_tail = 0ull, log2m_fix = 0ull;
         long long exp_sum = 0ll;
-        for (uint32_t p = lane; p < slices; p += 64) {
+        for (uint32_t p = lane; p < rows; p += 64) {
             const StatsExtra x = row[p];
             amax = x.absmax_bits > amax ? x.absmax_bits : amax;
             nonfinite += x.n_nonfinite;
@@ -360,12 +431,172 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
         exp_sum = wave_reduce_add(exp_sum);
         log2m_fix = wave_reduce_add(log2m_fix);
         if (lane == 0) {
-            const uint64_t lo = (uint64_t)bucket * bucket_elems;
-            const uint64_t hi = lo + bucket_elems < d ? lo + bucket_elems : d;
             const StatsExtra x{amax, nonfinite, n_tail, exp_sum, log2m_fix};
-            write_scalars(S, x, hi - lo, g_min);
+            write_scalars(S, x, n, g_min);
         }
     }
+}
+
+__global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
+    const char* __restrict__ ws, uint64_t ws_tensor_bytes, uint64_t ws_hist_bytes, uint32_t slices,
+    uint32_t groups_per_bucket, uint64_t d, uint64_t bucket_elems, float g_min, const MutPtrTable stats_tab)
+{
+    __shared__ uint32_t part[kReduceBlock];
+    const char* my_ws = ws + (uint64_t)blockIdx.y * ws_tensor_bytes;
+    const uint32_t* __restrict__ ws_hist = reinterpret_cast<const uint32_t*>(my_ws);
+    const StatsExtra* __restrict__ ws_extra = reinterpret_cast<const StatsExtra*>(my_ws + ws_hist_bytes);
+    tq_stats_t* __restrict__ stats = static_cast<tq_stats_t*>(stats_tab.p[blockIdx.y]);
+    const uint32_t blk = linear_block();
+    const uint32_t bucket = blk / groups_per_bucket;
+    const uint32_t grp = blk - bucket * groups_per_bucket;
+    if ((uint64_t)bucket * bucket_elems >= d) return;                  // padding of a folded grid
+    const uint64_t lo = (uint64_t)bucket * bucket_elems;
+    const uint64_t hi = lo + bucket_elems < d ? lo + bucket_elems : d;
+    reduce_rows(ws_hist, ws_extra, (uint64_t)bucket * slices, slices, grp, groups_per_bucket, stats + bucket,
+                hi - lo, g_min, part);
+}
+
+
+// ---- large buckets: the whole batch cut into equal shares ---------------------------------
+//
+// With buckets of 32768 elements or more the launch is `groups` workgroups (one per compute
+// unit for fp32, four for bf16) and the batch -- the tensors laid end to end, counted in tiles of
+// 4096 elements -- is cut into that many equal shares, whatever the buckets are: share w is the
+// tiles [w TT / groups, (w+1) TT / groups).  A workgroup takes the pieces of the buckets that
+// overlap its share one after the other.  A bucket that lies inside one share is written as a
+// finished record; the pieces of the others go to partial rows, numbered share + global bucket
+// index (from one piece to the next one of the two advances, so the number is unique and a
+// bucket's rows are consecutive), and a second kernel adds them.  Every workgroup reads the
+// same number of bytes, so the launch has no partly filled last round: with one bucket per
+// workgroup 8 x 119 buckets of 2^20 on 256 compute units took four rounds for 3.7 rounds' work.
+
+constexpr uint64_t kBalancedMinBucket = 32768;
+
+__host__ __device__ inline uint64_t share_start(uint64_t w, uint64_t total_tiles, uint32_t groups)
+{
+    return w * total_tiles / groups;
+}
+
+// The share that holds a tile: the largest w with share_start(w) <= tile.
+__host__ __device__ inline uint32_t share_of_tile(uint64_t tile, uint64_t total_tiles, uint32_t groups)
+{
+    return (uint32_t)(((tile + 1) * groups - 1) / total_tiles);
+}
+
+template <int DTYPE, bool TAIL>
+__global__ __launch_bounds__(kStatsBlock) void tq_stats_balanced_kernel(
+    const PtrTable g_tab, uint64_t d, uint64_t be, uint64_t nb, uint64_t tiles_per_tensor, uint64_t total_tiles,
+    float g_min, uint32_t* __restrict__ ws_hist, StatsExtra* __restrict__ ws_extra, const MutPtrTable stats_tab)
+{
+    const uint32_t w = blockIdx.x;
+    uint64_t tile = share_start(w, total_tiles, gridDim.x);
+    const uint64_t tile_end = share_start((uint64_t)w + 1, total_tiles, gridDim.x);
+    __shared__ StatsLds L;
+    bool first = true;
+    while (tile < tile_end) {                                          // one pass per tensor the share touches
+        const uint64_t t = tile / tiles_per_tensor, i = tile - t * tiles_per_tensor;
+        const uint64_t i_end = i + (tile_end - tile) < tiles_per_tensor ? i + (tile_end - tile) : tiles_per_tensor;
+        const uint64_t e0 = i * kStatsTile;
+        const uint64_t e1 = i_end * kStatsTile < d ? i_end * kStatsTile : d;
+        const void* __restrict__ g = g_tab.p[t];
+        tq_stats_t* __restrict__ stats = static_cast<tq_stats_t*>(stats_tab.p[t]);
+        for (uint64_t b = e0 / be; b * be < e1; ++b) {
+            const uint64_t lo = b * be, hi = lo + be < d ? lo + be : d;
+            const uint64_t cs = e0 > lo ? e0 : lo, ce = e1 < hi ? e1 : hi;
+            const bool whole = cs == lo && ce == hi;                   // no other share has a piece of this bucket
+            const uint64_t r = (uint64_t)w + t * nb + b;
+            if (!first) __syncthreads();                               // the histograms are cleared again
+            first = false;
+            const StatsExtra x = stats_slice<DTYPE, TAIL>(g, cs, ce, g_min, L, whole ? stats[b].hist : ws_hist + r * TQ_NBINS);
+            if (threadIdx.x == 0) {
+                if (whole) write_scalars(stats + b, x, hi - lo, g_min);
+                else ws_extra[r] = x;
+            }
+        }
+        tile += i_end - i;
+    }
+}
+
+// Adds the rows of the buckets that more than one share has a piece of.  One unit of
+// groups_per_bucket workgroups per bucket (by_boundary = 0), or -- when there are more buckets
+// than shares -- per boundary between two shares: the unit of boundary k takes the bucket the
+// boundary cuts, if it cuts one and if it is the first boundary inside that bucket.
+// The bucket a unit of the second kernel adds up, if any: tensor t, bucket b, its first row and
+// the number of rows.
+struct SplitBucket { uint64_t t, b, row0, n; uint32_t rows; bool any; };
+
+__device__ __forceinline__ SplitBucket split_bucket(uint64_t unit, uint32_t by_boundary, uint64_t d, uint64_t be, uint64_t nb,
+                                                    uint64_t tiles_per_tensor, uint64_t total_tiles, uint32_t groups)
+{
+    SplitBucket k{0, 0, 0, 0, 0, false};
+    if (by_boundary) {
+        const uint64_t tile = share_start(unit + 1, total_tiles, groups);
+        k.t = tile / tiles_per_tensor;
+        const uint64_t e = (tile - k.t * tiles_per_tensor) * kStatsTile;
+        k.b = e / be;
+        if (e == k.b * be) return k;                                   // the shares meet where a bucket (or tensor) begins
+    } else {
+        k.t = unit / nb;
+        k.b = unit - k.t * nb;
+    }
+    const uint64_t lo = k.b * be, hi = lo + be < d ? lo + be : d;
+    const uint32_t w0 = share_of_tile(k.t * tiles_per_tensor + lo / kStatsTile, total_tiles, groups);
+    const uint32_t w1 = share_of_tile(k.t * tiles_per_tensor + (hi - 1) / kStatsTile, total_tiles, groups);
+    if (w0 == w1) return k;                                            // written as a finished record already
+    if (by_boundary && w0 != unit) return k;                           // added at the first boundary inside it
+    k.row0 = (uint64_t)w0 + k.t * nb + k.b;
+    k.rows = w1 - w0 + 1;
+    k.n = hi - lo;
+    k.any = true;
+    return k;
+}
+
+// The same for buckets of a few rows each (at most kNarrowRows): one small workgroup per unit.
+constexpr int kNarrowBlock = 256;
+constexpr uint32_t kNarrowRows = 8;
+__global__ __launch_bounds__(kNarrowBlock) void tq_stats_balanced_reduce_narrow_kernel(
+    uint64_t d, uint64_t be, uint64_t nb, uint64_t tiles_per_tensor, uint64_t total_tiles, uint32_t groups,
+    uint32_t by_boundary, uint64_t n_units, float g_min,
+    const uint32_t* __restrict__ ws_hist, const StatsExtra* __restrict__ ws_extra, const MutPtrTable stats_tab)
+{
+    const uint64_t unit = linear_block();
+    if (unit >= n_units) return;                                       // padding of a folded grid
+    const SplitBucket k = split_bucket(unit, by_boundary, d, be, nb, tiles_per_tensor, total_tiles, groups);
+    if (!k.any) return;
+    tq_stats_t* __restrict__ S = static_cast<tq_stats_t*>(stats_tab.p[k.t]) + k.b;
+    for (int bin = threadIdx.x; bin < TQ_NBINS; bin += kNarrowBlock) {
+        uint32_t total = 0u;
+        for (uint32_t r = 0; r < k.rows; ++r) total += ws_hist[(k.row0 + r) * TQ_NBINS + bin];
+        S->hist[bin] = total;
+    }
+    if (threadIdx.x == 0) {
+        StatsExtra x{0u, 0u, 0ull, 0ll, 0ull};
+        for (uint32_t r = 0; r < k.rows; ++r) {
+            const StatsExtra y = ws_extra[k.row0 + r];
+            x.absmax_bits = y.absmax_bits > x.absmax_bits ? y.absmax_bits : x.absmax_bits;
+            x.n_nonfinite += y.n_nonfinite;
+            x.n_tail += y.n_tail;
+            x.exp_sum += y.exp_sum;
+            x.log2m_fix += y.log2m_fix;
+        }
+        write_scalars(S, x, k.n, g_min);
+    }
+}
+
+__global__ __launch_bounds__(kReduceBlock) void tq_stats_balanced_reduce_kernel(
+    uint64_t d, uint64_t be, uint64_t nb, uint64_t tiles_per_tensor, uint64_t total_tiles, uint32_t groups,
+    uint32_t by_boundary, uint64_t n_units, uint32_t groups_per_bucket, float g_min,
+    const uint32_t* __restrict__ ws_hist, const StatsExtra* __restrict__ ws_extra, const MutPtrTable stats_tab)
+{
+    __shared__ uint32_t part[kReduceBlock];
+    const uint32_t blk = linear_block();
+    const uint64_t unit = blk / groups_per_bucket;
+    const uint32_t grp = blk - (uint32_t)unit * groups_per_bucket;
+    if (unit >= n_units) return;                                       // padding of a folded grid
+    const SplitBucket k = split_bucket(unit, by_boundary, d, be, nb, tiles_per_tensor, total_tiles, groups);
+    if (!k.any) return;
+    reduce_rows(ws_hist, ws_extra, k.row0, k.rows, grp, groups_per_bucket,
+                static_cast<tq_stats_t*>(stats_tab.p[k.t]) + k.b, k.n, g_min, part);
 }
 
 
@@ -494,6 +725,13 @@ StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems, int count, uint64_t resi
     return p;
 }
 
+// Whether the launch is cut into equal shares (large buckets) or into buckets and their slices.
+bool uses_shares(uint64_t d, uint64_t bucket_elems)
+{
+    const uint64_t be = bucket_elems && bucket_elems < d ? bucket_elems : d;
+    return be >= tq::kBalancedMinBucket;
+}
+
 }  // namespace
 
 uint64_t tq_stats_workspace_bytes_impl(uint64_t d, uint64_t bucket_elems)
@@ -503,7 +741,12 @@ uint64_t tq_stats_workspace_bytes_impl(uint64_t d, uint64_t bucket_elems)
     const uint64_t nb = (d + be - 1) / be;
     const uint32_t slices = max_slices(be, nb);                        // no plan uses more
     const uint64_t hist_bytes = tq::stats_ws_hist_words(nb, slices) * 4;
-    const uint64_t bytes = (hist_bytes + 15) / 16 * 16 + nb * slices * sizeof(tq::StatsExtra);
+    uint64_t bytes = (hist_bytes + 15) / 16 * 16 + nb * slices * sizeof(tq::StatsExtra);
+    if (uses_shares(d, bucket_elems)) {
+        // one row per share and per bucket; a batch of `count` tensors has count times this much
+        const uint64_t shared = (tq::kStatsResidentGroups + nb) * (TQ_NBINS * 4 + sizeof(tq::StatsExtra));
+        bytes = bytes > shared ? bytes : shared;
+    }
     return (bytes + 255) / 256 * 256;                                  // regions of a batch stay aligned
 }
 
@@ -534,12 +777,56 @@ hipError_t tq_stats_static_scratch(void** out)
 hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t d, uint64_t bucket_elems,
                            float g_min, tq_stats_t* const* stats, void* workspace, hipStream_t st)
 {
+    if (count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
     // bf16 elements cost half the bytes but all the instructions: that kernel is bound by issue and
     // wants every wavefront slot, the fp32 ones are bound by memory and want the fewest flushes
-    const StatsPlan p = plan_stats(d, bucket_elems, count, dtype == TQ_BF16 ? tq::kStatsResidentGroups : tq::kStatsTargetGroups);
+    const uint64_t resident = dtype == TQ_BF16 ? tq::kStatsResidentGroups : tq::kStatsTargetGroups;
+    if (uses_shares(d, bucket_elems)) {
+        tq::PtrTable gt{};
+        tq::MutPtrTable stt{};
+        for (int i = 0; i < count; ++i) { gt.p[i] = g[i]; stt.p[i] = stats[i]; }
+        const uint64_t be = bucket_elems ? bucket_elems : d;
+        const uint64_t nb = (d + be - 1) / be;
+        const uint64_t tiles_per_tensor = (d + tq::kStatsTile - 1) / tq::kStatsTile;
+        const uint64_t total_tiles = tiles_per_tensor * (uint64_t)count;
+        const uint64_t fit = total_tiles * tq::kStatsTile / tq::kStatsMinSlice;   // shares of at least 16384 elements
+        const uint32_t groups = (uint32_t)(fit < 1 ? 1 : (fit < resident ? fit : resident));
+        const uint64_t rows = groups + nb * (uint64_t)count;
+        uint32_t* ws_hist = static_cast<uint32_t*>(workspace);
+        tq::StatsExtra* ws_extra = reinterpret_cast<tq::StatsExtra*>(static_cast<char*>(workspace) + rows * TQ_NBINS * 4);
+#define TQ_LAUNCH_SHARES(DT, TL)                                                                                  \
+    hipLaunchKernelGGL((tq::tq_stats_balanced_kernel<DT, TL>), dim3(groups), dim3(tq::kStatsBlock), 0, st, gt, d, be, \
+                       nb, tiles_per_tensor, total_tiles, g_min, ws_hist, ws_extra, stt)
+        if (dtype == TQ_F32) {
+            if (g_min > 0.0f) { TQ_LAUNCH_SHARES(TQ_F32, true); } else { TQ_LAUNCH_SHARES(TQ_F32, false); }
+        } else {
+            if (g_min > 0.0f) { TQ_LAUNCH_SHARES(TQ_BF16, true); } else { TQ_LAUNCH_SHARES(TQ_BF16, false); }
+        }
+#undef TQ_LAUNCH_SHARES
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess || groups == 1) return err;
+        const uint32_t gpb = (TQ_NBINS + tq::kReduceBins - 1) / tq::kReduceBins + 1;
+        const uint64_t n_buckets = nb * (uint64_t)count;
+        const uint32_t by_boundary = n_buckets > groups - 1 ? 1u : 0u;
+        const uint64_t n_units = by_boundary ? groups - 1 : n_buckets;
+        dim3 rgrid;
+        // rows of a bucket: one per share it reaches into
+        const uint64_t share_tiles = total_tiles / groups, bucket_tiles = (be < d ? be : d) / tq::kStatsTile + 2;
+        if (bucket_tiles / share_tiles + 2 <= tq::kNarrowRows) {
+            if (!tq::fold_grid(n_units, tq::kNarrowBlock, 1, rgrid)) return hipErrorInvalidValue;
+            hipLaunchKernelGGL(tq::tq_stats_balanced_reduce_narrow_kernel, rgrid, dim3(tq::kNarrowBlock), 0, st, d, be, nb,
+                               tiles_per_tensor, total_tiles, groups, by_boundary, n_units, g_min, ws_hist, ws_extra, stt);
+            return hipGetLastError();
+        }
+        if (!tq::fold_grid(n_units * gpb, tq::kReduceBlock, 1, rgrid)) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(tq::tq_stats_balanced_reduce_kernel, rgrid, dim3(tq::kReduceBlock), 0, st, d, be, nb,
+                           tiles_per_tensor, total_tiles, groups, by_boundary, n_units, gpb, g_min, ws_hist, ws_extra, stt);
+        return hipGetLastError();
+    }
+    const StatsPlan p = plan_stats(d, bucket_elems, count, resident);
     const uint64_t nblocks = p.nb * p.slices;
     dim3 pgrid;
-    if (count < 1 || count > tq::kMaxBatch || !tq::fold_grid(nblocks, tq::kStatsBlock, (unsigned)count, pgrid))
+    if (!tq::fold_grid(nblocks, tq::kStatsBlock, (unsigned)count, pgrid))
         return hipErrorInvalidValue;
     const uint64_t hist_bytes = (tq::stats_ws_hist_words(p.nb, p.slices) * 4 + 15) / 16 * 16;
     const uint64_t tensor_bytes = tq_stats_workspace_bytes_impl(d, bucket_elems);
