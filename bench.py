@@ -100,15 +100,17 @@ class Path:
         self.out = torch.empty(self.d, dtype=torch.float32, device="cuda")
         self.step_no = 0
         # per-layer quantization: one record per layer of the workload's recipe instead of per bucket,
-        # through the *_segments entry points (one launch per worker and stage)
+        # through the *_segments entry points
         self.seg = None
         if segments:
             self.seg = B.Segments(synth.layer_segments(wl, self.d))
-            self.mode = mode = "per-worker"
             self.stats = [torch.empty(self.seg.nseg * B.STATS_BYTES, dtype=torch.uint8, device="cuda") for _ in range(self.N)]
             self.params = [torch.empty(self.seg.nseg * B.PARAMS_BYTES, dtype=torch.uint8, device="cuda") for _ in range(self.N)]
-            self.ws = [torch.empty(B.stats_segments_workspace_bytes(self.d, self.seg.nseg), dtype=torch.uint8,
-                                   device="cuda")] * self.N
+            self.ws_all = torch.empty(self.N * B.stats_segments_workspace_bytes(self.d, self.seg.nseg), dtype=torch.uint8,
+                                      device="cuda")
+            self.ws = [self.ws_all] * self.N             # one stream: the per-worker launches run in turn
+            if mode == "streams":
+                raise SystemExit("--segments runs batched or per-worker")
 
     def describe(self):
         torch = self.torch
@@ -137,12 +139,17 @@ class Path:
         self.B.tq_decompress_aggregate(self.pay, self.params, self.out, self.bits, self.be)
 
     def stats_all(self):
+        if self.seg is not None:
+            return self.B.tq_stats_segments_multi(self.g, self.seg, self.stats, self.ws_all, self.wl.g_min)
         self.B.tq_stats_multi(self.g, self.stats, self.ws_all, self.be, self.wl.g_min)
 
     def params_all(self):
         self.B.tq_params_multi(self.stats, self.params, self.bits, self.grid)
 
     def compress_all(self):
+        if self.seg is not None:
+            return self.B.tq_compress_segments_multi(self.g, self.seg, self.params, self.pay, self.bits, 0x5EED, 0,
+                                                     self.step_no)
         self.B.tq_compress_multi(self.g, self.params, self.pay, self.bits, 0x5EED, 0, self.step_no, self.be, self.grid)
 
     def step(self):
@@ -429,7 +436,7 @@ def main():
             del p2
             torch.cuda.empty_cache()
         # config 4 once more with one record per LAYER of its recipe (variable-size segments)
-        p2 = Path(synth.WORKLOADS["cfg4"], 2, 0, "per-worker", max(1, a.buffer_sets), segments=True)
+        p2 = Path(synth.WORKLOADS["cfg4"], 2, 0, "batched", max(1, a.buffer_sets), segments=True)
         torch.cuda.synchronize()
         r = measure(p2, a.other_steps, 3, 0)
         r["roofline"] = compress_roofline(p2, r)

@@ -256,6 +256,12 @@ int tq_quantize_dequantize(const void* g_dev, int dtype, uint64_t d, uint64_t bu
  *   workspace_dev     tq_stats_segments_workspace_bytes(d, nseg) bytes, rules as for tq_stats
  * tq_compress_segments takes no `grid`: it has one launch shape.  The segment kernels favour
  * generality over the last tenth of speed (one tile per workgroup, plain level tables).
+ * tq_stats_segments needs d < 2^32 (the counts of a record are 32-bit).
+ * The *_multi forms take `count` tensors of the same d and dtype that share ONE segment table
+ * (the N workers' gradients of one model) in one launch each, as tq_stats_multi and
+ * tq_compress_multi do for buckets: host arrays of `count` device pointers, tensor i of
+ * tq_compress_segments_multi is worker first_worker + i, the workspace is count *
+ * tq_stats_segments_workspace_bytes(d, nseg) bytes, results are identical to `count` single calls.
  */
 uint64_t tq_stats_segments_workspace_bytes(uint64_t d, uint64_t nseg);
 int tq_stats_segments(const void* g_dev, int dtype, uint64_t d, const uint64_t* seg_offsets_dev,
@@ -266,6 +272,15 @@ int tq_compress_segments(const void* g_dev, int dtype, uint64_t d, const uint64_
                          const uint64_t* seg_offsets_host, uint64_t nseg,
                          const tq_params_t* params_dev, int bits, uint64_t seed, uint32_t worker,
                          uint32_t step, void* payload_dev, void* stream);
+int tq_stats_segments_multi(const void* const* g_host, int count, int dtype, uint64_t d,
+                            const uint64_t* seg_offsets_dev, const uint64_t* seg_offsets_host,
+                            uint64_t nseg, float g_min, tq_stats_t* const* stats_host,
+                            void* workspace_dev, uint64_t workspace_bytes, void* stream);
+int tq_compress_segments_multi(const void* const* g_host, int count, int dtype, uint64_t d,
+                               const uint64_t* seg_offsets_dev, const uint64_t* seg_offsets_host,
+                               uint64_t nseg, const tq_params_t* const* params_host, int bits,
+                               uint64_t seed, uint32_t first_worker, uint32_t step,
+                               void* const* payload_host, void* stream);
 int tq_decompress_aggregate_segments(const void* const* payload_host,
                                      const tq_params_t* const* params_host,
                                      const float* weights_host, int N, uint64_t d,

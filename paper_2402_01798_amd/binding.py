@@ -77,7 +77,10 @@ def lib():
         L.tq_stats_segments.argtypes = [vp, i32, u64, vp, vp, u64, f32, vp, vp, u64, vp]
         L.tq_compress_segments.argtypes = [vp, i32, u64, vp, vp, u64, vp, i32, u64, u32, u32, vp, vp]
         L.tq_decompress_aggregate_segments.argtypes = [vp, vp, vp, i32, u64, vp, vp, u64, i32, i32, vp, vp]
-        for f in (L.tq_stats_segments, L.tq_compress_segments, L.tq_decompress_aggregate_segments):
+        L.tq_stats_segments_multi.argtypes = [vp, i32, i32, u64, vp, vp, u64, f32, vp, vp, u64, vp]
+        L.tq_compress_segments_multi.argtypes = [vp, i32, i32, u64, vp, vp, u64, vp, i32, u64, u32, u32, vp, vp]
+        for f in (L.tq_stats_segments, L.tq_compress_segments, L.tq_decompress_aggregate_segments,
+                  L.tq_stats_segments_multi, L.tq_compress_segments_multi):
             f.restype = i32
         for f in (L.tq_stats, L.tq_stats_static, L.tq_params, L.tq_compress, L.tq_decompress_aggregate,
                   L.tq_decompress_aggregate_update, L.tq_stats_multi, L.tq_params_multi, L.tq_compress_multi):
@@ -300,6 +303,29 @@ def tq_compress_segments(g, seg, params, payload, bits, seed, worker, step):
                                       bits, seed, worker, step, _dev(payload, "payload"), _stream()),
            "tq_compress_segments")
     return payload
+
+
+def tq_stats_segments_multi(gs, seg, stats, workspace, g_min=0.0):
+    """Batched tq_stats_segments: same-shaped gradients that share the segment table."""
+    dev, host, nseg = seg.args()
+    _check(lib().tq_stats_segments_multi(_ptr_array(gs, "g"), len(gs), _dtype_code(gs[0]), gs[0].numel(), dev, host,
+                                         nseg, g_min, _ptr_array(stats, "stats"), _dev(workspace, "workspace"),
+                                         workspace.numel(), _stream()), "tq_stats_segments_multi")
+    return stats
+
+
+def tq_compress_segments_multi(gs, seg, params, payloads, bits, seed, first_worker, step):
+    d = gs[0].numel()
+    for g, q, p in zip(gs, params, payloads):
+        if g.numel() != d or g.dtype != gs[0].dtype:
+            raise ValueError("batched tensors must share shape and dtype")
+        if q.numel() != seg.nseg * PARAMS_BYTES or p.numel() < payload_bytes(d, bits):
+            raise ValueError("params / payload buffer size does not match the segments")
+    dev, host, nseg = seg.args()
+    _check(lib().tq_compress_segments_multi(_ptr_array(gs, "g"), len(gs), _dtype_code(gs[0]), d, dev, host, nseg,
+                                            _ptr_array(params, "params"), bits, seed, first_worker, step,
+                                            _ptr_array(payloads, "payload"), _stream()), "tq_compress_segments_multi")
+    return payloads
 
 
 def tq_decompress_aggregate_segments(payloads, params, seg, out, bits, weights=None, accumulate=False):

@@ -23,14 +23,16 @@ hipError_t tq_launch_simulate(const void* g, int dtype, uint64_t d, uint64_t buc
                               hipStream_t st);
 
 uint64_t tq_stats_segments_workspace_bytes_impl(uint64_t d, uint64_t nseg);
-hipError_t tq_launch_stats_segments(const void* g, int dtype, uint64_t d, const uint64_t* seg_off, uint64_t nseg,
-                                    float g_min, tq_stats_t* stats, void* workspace, hipStream_t st);
-hipError_t tq_launch_compress_segments(const void* g, int dtype, uint64_t d, const uint64_t* seg_off, uint64_t nseg,
-                                       const tq_params_t* params, int bits, uint64_t seed, uint32_t worker,
-                                       uint32_t step, void* payload, hipStream_t st);
+hipError_t tq_launch_stats_segments(const void* const* g, int count, int dtype, uint64_t d, const uint64_t* seg_off,
+                                    uint64_t nseg, float g_min, tq_stats_t* const* stats, void* workspace,
+                                    hipStream_t st);
+hipError_t tq_launch_compress_segments(const void* const* g, int count, int dtype, uint64_t d, const uint64_t* seg_off,
+                                       const uint64_t* seg_host, uint64_t nseg, const tq_params_t* const* params, int bits, uint64_t seed,
+                                       uint32_t first_worker, uint32_t step, void* const* payload, hipStream_t st);
 hipError_t tq_launch_decode_segments(const void* const* payload, const tq_params_t* const* params,
                                      const float* weights, int N, uint64_t d, const uint64_t* seg_off,
-                                     uint64_t nseg, int bits, int accumulate, float* out, hipStream_t st);
+                                     const uint64_t* seg_host, uint64_t nseg, int bits, int accumulate, float* out,
+                                     hipStream_t st);
 
 static_assert(sizeof(tq_stats_t) == 3632, "tq_stats_t layout is part of the interface");
 static_assert(sizeof(tq_params_t) == 160, "tq_params_t layout is part of the interface");
@@ -246,32 +248,60 @@ uint64_t tq_stats_segments_workspace_bytes(uint64_t d, uint64_t nseg)
     return tq_stats_segments_workspace_bytes_impl(d, nseg);
 }
 
+int tq_stats_segments_multi(const void* const* g_host, int count, int dtype, uint64_t d,
+                            const uint64_t* seg_offsets_dev, const uint64_t* seg_offsets_host, uint64_t nseg,
+                            float g_min, tq_stats_t* const* stats_host, void* workspace_dev, uint64_t workspace_bytes,
+                            void* stream)
+{
+    int rc;
+    if ((rc = check_segments(d, seg_offsets_dev, seg_offsets_host, nseg)) || (rc = check_dtype(dtype))) return rc;
+    if (count < 1 || !g_host || !stats_host || !workspace_dev) return TQ_EINVAL;
+    if (count > TQ_MAX_WORKERS || nseg * (uint64_t)count > 0xFFFFFFFFull) return TQ_EUNSUPPORTED;
+    if (d > 0xFFFFFFFFull) return TQ_EUNSUPPORTED;          // the counts of tq_stats_t are 32-bit
+    if (workspace_bytes < (uint64_t)count * tq_stats_segments_workspace_bytes_impl(d, nseg)) return TQ_EINVAL;
+    if (g_min != g_min || (g_min > 0.0f && g_min < 9.094947017729282e-13f) || g_min > 3.0e38f) return TQ_EINVAL;
+    if (!aligned16(workspace_dev)) return TQ_EALIGN;
+    for (int i = 0; i < count; ++i) {
+        if (!g_host[i] || !stats_host[i]) return TQ_EINVAL;
+        if (!aligned16(g_host[i]) || !aligned16(stats_host[i])) return TQ_EALIGN;
+    }
+    return from_hip(tq_launch_stats_segments(g_host, count, dtype, d, seg_offsets_dev, nseg, g_min, stats_host,
+                                             workspace_dev, static_cast<hipStream_t>(stream)));
+}
+
 int tq_stats_segments(const void* g_dev, int dtype, uint64_t d, const uint64_t* seg_offsets_dev,
                       const uint64_t* seg_offsets_host, uint64_t nseg, float g_min, tq_stats_t* stats_dev,
                       void* workspace_dev, uint64_t workspace_bytes, void* stream)
 {
+    return tq_stats_segments_multi(&g_dev, 1, dtype, d, seg_offsets_dev, seg_offsets_host, nseg, g_min, &stats_dev,
+                                   workspace_dev, workspace_bytes, stream);
+}
+
+int tq_compress_segments_multi(const void* const* g_host, int count, int dtype, uint64_t d,
+                               const uint64_t* seg_offsets_dev, const uint64_t* seg_offsets_host, uint64_t nseg,
+                               const tq_params_t* const* params_host, int bits, uint64_t seed, uint32_t first_worker,
+                               uint32_t step, void* const* payload_host, void* stream)
+{
     int rc;
-    if ((rc = check_segments(d, seg_offsets_dev, seg_offsets_host, nseg)) || (rc = check_dtype(dtype))) return rc;
-    if (!g_dev || !stats_dev || !workspace_dev) return TQ_EINVAL;
-    if (workspace_bytes < tq_stats_segments_workspace_bytes_impl(d, nseg)) return TQ_EINVAL;
-    if (g_min != g_min || (g_min > 0.0f && g_min < 9.094947017729282e-13f) || g_min > 3.0e38f) return TQ_EINVAL;
-    if (!aligned16(g_dev) || !aligned16(stats_dev) || !aligned16(workspace_dev)) return TQ_EALIGN;
-    return from_hip(tq_launch_stats_segments(g_dev, dtype, d, seg_offsets_dev, nseg, g_min, stats_dev, workspace_dev,
-                                             static_cast<hipStream_t>(stream)));
+    if ((rc = check_segments(d, seg_offsets_dev, seg_offsets_host, nseg)) || (rc = check_dtype(dtype)) ||
+        (rc = check_bits(bits)))
+        return rc;
+    if (count < 1 || !g_host || !params_host || !payload_host) return TQ_EINVAL;
+    if (count > TQ_MAX_WORKERS) return TQ_EUNSUPPORTED;
+    for (int i = 0; i < count; ++i) {
+        if (!g_host[i] || !params_host[i] || !payload_host[i]) return TQ_EINVAL;
+        if (!aligned16(g_host[i]) || !aligned16(params_host[i]) || !aligned16(payload_host[i])) return TQ_EALIGN;
+    }
+    return from_hip(tq_launch_compress_segments(g_host, count, dtype, d, seg_offsets_dev, seg_offsets_host, nseg, params_host, bits, seed,
+                                                first_worker, step, payload_host, static_cast<hipStream_t>(stream)));
 }
 
 int tq_compress_segments(const void* g_dev, int dtype, uint64_t d, const uint64_t* seg_offsets_dev,
                          const uint64_t* seg_offsets_host, uint64_t nseg, const tq_params_t* params_dev, int bits,
                          uint64_t seed, uint32_t worker, uint32_t step, void* payload_dev, void* stream)
 {
-    int rc;
-    if ((rc = check_segments(d, seg_offsets_dev, seg_offsets_host, nseg)) || (rc = check_dtype(dtype)) ||
-        (rc = check_bits(bits)))
-        return rc;
-    if (!g_dev || !params_dev || !payload_dev) return TQ_EINVAL;
-    if (!aligned16(g_dev) || !aligned16(params_dev) || !aligned16(payload_dev)) return TQ_EALIGN;
-    return from_hip(tq_launch_compress_segments(g_dev, dtype, d, seg_offsets_dev, nseg, params_dev, bits, seed, worker,
-                                                step, payload_dev, static_cast<hipStream_t>(stream)));
+    return tq_compress_segments_multi(&g_dev, 1, dtype, d, seg_offsets_dev, seg_offsets_host, nseg, &params_dev, bits,
+                                      seed, worker, step, &payload_dev, stream);
 }
 
 int tq_decompress_aggregate_segments(const void* const* payload_host, const tq_params_t* const* params_host,
@@ -282,7 +312,8 @@ int tq_decompress_aggregate_segments(const void* const* payload_host, const tq_p
     int rc;
     if ((rc = check_segments(d, seg_offsets_dev, seg_offsets_host, nseg))) return rc;
     if ((rc = check_decode(payload_host, params_host, weights_host, N, d, 0, bits, out_dev))) return rc;
-    return from_hip(tq_launch_decode_segments(payload_host, params_host, weights_host, N, d, seg_offsets_dev, nseg,
+    return from_hip(tq_launch_decode_segments(payload_host, params_host, weights_host, N, d, seg_offsets_dev,
+                                              seg_offsets_host, nseg,
                                               bits, accumulate ? 1 : 0, out_dev, static_cast<hipStream_t>(stream)));
 }
 

@@ -272,6 +272,8 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
     const uint64_t lim = bend < d ? bend : d;
     if (gbase + (uint64_t)T * kTile <= lim) {
         // every lane owns a whole group in every tile: all reads first, the draws under them
+        // (requesting the reads even earlier, before the codebook is set up, was slower: 708 us
+        // against 668 on 8 x 124 M fp32)
         float x[T][8];
         uint32_t rw[T][4];
 #pragma unroll
@@ -334,22 +336,84 @@ __global__ __launch_bounds__(kBlock) void tq_compress_kernel(
 // the segment index stays inside [0, nseg) and every element access is bounded by d.
 template <int DTYPE, int BITS>
 __global__ __launch_bounds__(kBlock) void tq_compress_segments_kernel(
-    const void* __restrict__ g, uint64_t d, uint64_t d_pad, const uint64_t* __restrict__ seg_off, uint32_t nseg,
-    const tq_params_t* __restrict__ params, uint32_t seed_lo, uint32_t seed_hi, uint32_t worker, uint32_t step,
-    uint8_t* __restrict__ payload, uint64_t payload_bytes)
+    const PtrTable g_tab, uint64_t d, uint64_t d_pad, const uint64_t* __restrict__ seg_off, uint32_t nseg,
+    const SegHints hints, const PtrTable params_tab, uint32_t seed_lo, uint32_t seed_hi, uint32_t first_worker, uint32_t step,
+    const MutPtrTable payload_tab, uint64_t payload_bytes)
 {
     const uint64_t ebase = (uint64_t)linear_block() * kTile;
     if (ebase >= d_pad) return;                                // padding of a folded grid
-    const uint64_t tile_end = ebase + kTile < d_pad ? ebase + kTile : d_pad;
+    // blockIdx.y = tensor of the batch; its worker id keys the random draws
+    const void* __restrict__ g = g_tab.p[blockIdx.y];
+    const tq_params_t* __restrict__ params = static_cast<const tq_params_t*>(params_tab.p[blockIdx.y]);
+    uint8_t* __restrict__ payload = static_cast<uint8_t*>(payload_tab.p[blockIdx.y]);
+    const uint32_t worker = first_worker + blockIdx.y;
+    // positions inside the tile are 32-bit offsets from its first element (which is the same for
+    // the whole workgroup): the tensor's end, the payload's end and the segments' ends as such
     const uint32_t lane = threadIdx.x;
-    const uint64_t e0 = ebase + (uint64_t)lane * kGroup;
-    const uint64_t byte_off = (e0 >> 3) * (uint64_t)BITS;
+    const uint32_t rel = lane * kGroup;                                              // this lane's group
+    const uint32_t tile_len = (uint32_t)(ebase + kTile < d_pad ? kTile : d_pad - ebase);   // multiple of 128
+    const uint32_t d_rel = ebase < d ? (uint32_t)(d - ebase < (uint64_t)kTile ? d - ebase : kTile) : 0u;
+    const uint64_t tile_byte = (ebase >> 3) * (uint64_t)BITS;                         // payload offset of the tile
+    const uint32_t pay_rel =                                                          // payload bytes from there on, capped
+        tile_byte < payload_bytes ? (uint32_t)(payload_bytes - tile_byte < (uint64_t)kTile ? payload_bytes - tile_byte : kTile) : 0u;
+    const uint32_t byte_rel = lane * (uint32_t)BITS;
     __shared__ LevelLds tab;
 
-    uint32_t s = find_segment(seg_off, nseg, ebase < d ? ebase : d - 1);
+    // The lane's group and its draws depend on its position alone: the values are requested and
+    // the draws computed before the segment is looked up (a chain of dependent scalar loads).
+    const int n_valid = rel >= d_rel ? 0 : (d_rel - rel >= (uint32_t)kGroup ? kGroup : (int)(d_rel - rel));
+    float x[8];
+    if (n_valid == kGroup) {
+        load_group<DTYPE, false>(g, ebase + rel, x);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, ebase + rel + j) : 0.0f;
+    }
+    uint32_t rw[4];
+    {
+        // one Philox call per lane; the high counter word stays scalar unless the low word wraps inside the tile
+        const uint64_t qb = ebase >> 3;
+        const uint32_t qb_lo = (uint32_t)qb, qb_hi = (uint32_t)(qb >> 32);
+        const uint32_t q_lo = qb_lo + lane;
+        if (qb_lo <= 0xFFFFFFFFu - kBlock) philox4x32_10(q_lo, qb_hi, worker, step, seed_lo, seed_hi, rw);
+        else philox4x32_10(q_lo, qb_hi + (q_lo < qb_lo ? 1u : 0u), worker, step, seed_lo, seed_hi, rw);
+        asm volatile("" : "+v"(rw[0]));                        // computed here, under the loads
+    }
+
+    uint32_t s = find_segment(seg_off, nseg, ebase < d ? ebase : d - 1, hints);
+    replace_nan(x);
+    {
+        // Nearly every tile lies inside one segment, with all its groups whole and its codes inside
+        // the payload: straight-line code, as for a bucket.  The test uses the very segment ends
+        // the loop below would use, so both ways write the same bytes.
+        const uint64_t seg_lo = seg_off[s];
+        const uint64_t seg_hi = s + 1 < nseg ? seg_off[s + 1] : d_pad;
+        if (seg_lo <= ebase && seg_hi >= ebase + kTile && d_rel == (uint32_t)kTile &&
+            pay_rel >= (uint32_t)kBlock * (uint32_t)BITS) {
+            const tq_params_t* P = params + s;
+            const float alpha = P->alpha;
+            const float inv_step = P->inv_w[0];
+            float lv[16];
+            uint32_t word;
+            if (P->grid != TQ_GRID_UNIFORM) {                  // uniform over the workgroup
+                fill_level_lds(tab, P, (1u << BITS) - 1u);
+#pragma unroll
+                for (int j = 0; j < 16; ++j) lv[j] = P->level[j];
+                __syncthreads();
+                word = encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab);
+            } else {
+                word = encode_group<BITS, TQ_GRID_UNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab);
+            }
+            store_codes<BITS>(payload + tile_byte + byte_rel, word);
+            return;
+        }
+    }
     for (;;) {
         const uint64_t seg_lo = seg_off[s];
         const uint64_t seg_hi = s + 1 < nseg ? seg_off[s + 1] : d_pad;
+        // the part of the tile that belongs to this segment, as offsets from the tile's start
+        const uint32_t lo_rel = (uint32_t)(seg_lo > ebase ? (seg_lo - ebase < (uint64_t)tile_len ? seg_lo - ebase : tile_len) : 0);
+        const uint32_t hi_rel = (uint32_t)(seg_hi > ebase ? (seg_hi - ebase < (uint64_t)tile_len ? seg_hi - ebase : tile_len) : 0);
         const tq_params_t* P = params + s;
         float lv[16];
         const float alpha = P->alpha;
@@ -361,31 +425,17 @@ __global__ __launch_bounds__(kBlock) void tq_compress_segments_kernel(
             for (int j = 0; j < 16; ++j) lv[j] = P->level[j];   // wave-uniform: scalar loads
             __syncthreads();
         }
-        if (e0 >= seg_lo && e0 < seg_hi && e0 < tile_end && byte_off < payload_bytes) {
+        if (rel >= lo_rel && rel < hi_rel && byte_rel < pay_rel) {
             uint32_t word = 0;                                 // a group wholly in the padding encodes as 0
-            if (e0 < d) {
-                const int n_valid = d - e0 >= (uint64_t)kGroup ? kGroup : (int)(d - e0);
-                float x[8];
-                if (n_valid == kGroup) {
-                    load_group<DTYPE, false>(g, e0, x);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) x[j] = (j < n_valid) ? load_one<DTYPE>(g, e0 + j) : 0.0f;
-                }
-                const uint64_t q = e0 >> 3;
-                uint32_t rw[4];
-                philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), worker, step, seed_lo, seed_hi, rw);
-                replace_nan(x);
-                if (n_valid == kGroup)
-                    word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab)
-                                      : encode_group<BITS, TQ_GRID_UNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab);
-                else
-                    word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab)
-                                      : encode_group<BITS, TQ_GRID_UNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab);
-            }
-            store_codes<BITS>(payload + byte_off, word, payload_bytes - byte_off);
+            if (n_valid == kGroup)
+                word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab)
+                                  : encode_group<BITS, TQ_GRID_UNIFORM, false>(x, rw, 8, alpha, inv_step, lv, tab);
+            else if (n_valid > 0)
+                word = nonuniform ? encode_group<BITS, TQ_GRID_NONUNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab)
+                                  : encode_group<BITS, TQ_GRID_UNIFORM, true>(x, rw, n_valid, alpha, inv_step, lv, tab);
+            store_codes<BITS>(payload + tile_byte + byte_rel, word, (uint64_t)(pay_rel - byte_rel));
         }
-        if (seg_hi >= tile_end || s + 1 >= nseg) break;
+        if (hi_rel >= tile_len || s + 1 >= nseg) break;
         ++s;
         __syncthreads();                                       // before the next segment's table replaces this one
     }
@@ -561,20 +611,26 @@ hipError_t tq_launch_simulate(const void* g, int dtype, uint64_t d, uint64_t buc
 
 
 // Host side of tq_compress_segments after the argument checks of the C entry point.
-hipError_t tq_launch_compress_segments(const void* g, int dtype, uint64_t d, const uint64_t* seg_off, uint64_t nseg,
-                                       const tq_params_t* params, int bits, uint64_t seed, uint32_t worker,
-                                       uint32_t step, void* payload, hipStream_t st)
+hipError_t tq_launch_compress_segments(const void* const* g, int count, int dtype, uint64_t d, const uint64_t* seg_off,
+                                       const uint64_t* seg_host, uint64_t nseg, const tq_params_t* const* params, int bits, uint64_t seed,
+                                       uint32_t first_worker, uint32_t step, void* const* payload, hipStream_t st)
 {
     const uint64_t d_pad = (d + 127) / 128 * 128;
     const uint64_t nblocks = (d_pad + tq::kTile - 1) / tq::kTile;
     dim3 blocks;
-    if (nseg > 0xFFFFFFFFull || !tq::fold_grid(nblocks, tq::kBlock, 1, blocks)) return hipErrorInvalidValue;
+    if (count < 1 || count > tq::kMaxBatch || nseg > 0xFFFFFFFFull ||
+        !tq::fold_grid(nblocks, tq::kBlock, (unsigned)count, blocks))
+        return hipErrorInvalidValue;
+    tq::PtrTable gt{}, pt{};
+    tq::MutPtrTable yt{};
+    for (int i = 0; i < count; ++i) { gt.p[i] = g[i]; pt.p[i] = params[i]; yt.p[i] = payload[i]; }
     const uint32_t slo = (uint32_t)seed, shi = (uint32_t)(seed >> 32);
     const uint64_t pbytes = tq_payload_bytes(d, bits);
     const dim3 threads(tq::kBlock);
-#define TQ_LAUNCH_CSEG(DT, B)                                                                                  \
-    hipLaunchKernelGGL((tq::tq_compress_segments_kernel<DT, B>), blocks, threads, 0, st, g, d, d_pad, seg_off, \
-                       (uint32_t)nseg, params, slo, shi, worker, step, static_cast<uint8_t*>(payload), pbytes)
+    const tq::SegHints hints = tq::make_seg_hints(seg_host, nseg, d);
+#define TQ_LAUNCH_CSEG(DT, B)                                                                                   \
+    hipLaunchKernelGGL((tq::tq_compress_segments_kernel<DT, B>), blocks, threads, 0, st, gt, d, d_pad, seg_off, \
+                       (uint32_t)nseg, hints, pt, slo, shi, first_worker, step, yt, pbytes)
 #define TQ_LAUNCH_CSEG_B(DT)                      \
     switch (bits) {                               \
         case 2: TQ_LAUNCH_CSEG(DT, 2); break;     \

@@ -358,8 +358,8 @@ __global__ __launch_bounds__(kBlock) void tq_decode_kernel(
 template <int BITS, int MODE>
 __global__ __launch_bounds__(kBlock) void tq_decode_segments_kernel(
     const DecodeArgs args, int N, int weighted, float scale, uint64_t d, uint64_t d_pad,
-    const uint64_t* __restrict__ seg_off, uint32_t nseg, uint64_t payload_bytes, float* __restrict__ out,
-    const Update up)
+    const uint64_t* __restrict__ seg_off, uint32_t nseg, const SegHints hints, uint64_t payload_bytes,
+    float* __restrict__ out, const Update up)
 {
     constexpr uint32_t MASK = (1u << BITS) - 1u;
     const uint64_t ebase = (uint64_t)linear_block() * kTile;
@@ -368,7 +368,7 @@ __global__ __launch_bounds__(kBlock) void tq_decode_segments_kernel(
     const uint64_t e0 = ebase + (uint64_t)threadIdx.x * kGroup;
     __shared__ float table[TQ_MAX_WORKERS * 16];
 
-    uint32_t s = find_segment(seg_off, nseg, ebase);
+    uint32_t s = find_segment(seg_off, nseg, ebase, hints);
     for (;;) {
         const uint64_t seg_lo = seg_off[s];
         const uint64_t seg_hi = s + 1 < nseg ? seg_off[s + 1] : d_pad;
@@ -515,8 +515,10 @@ hipError_t tq_launch_decode(const void* const* payload, const tq_params_t* const
 // Host side of tq_decompress_aggregate_segments after the argument checks of the C entry point.
 hipError_t tq_launch_decode_segments(const void* const* payload, const tq_params_t* const* params,
                                      const float* weights, int N, uint64_t d, const uint64_t* seg_off,
-                                     uint64_t nseg, int bits, int accumulate, float* out, hipStream_t st)
+                                     const uint64_t* seg_host, uint64_t nseg, int bits, int accumulate, float* out,
+                                     hipStream_t st)
 {
+    const tq::SegHints hints = tq::make_seg_hints(seg_host, nseg, d);
     tq::DecodeArgs args;
     for (int i = 0; i < TQ_MAX_WORKERS; ++i) {
         args.payload[i] = i < N ? static_cast<const uint8_t*>(payload[i]) : nullptr;
@@ -534,7 +536,7 @@ hipError_t tq_launch_decode_segments(const void* const* payload, const tq_params
     const dim3 threads(tq::kBlock);
 #define TQ_LAUNCH_DSEG(B, M)                                                                                   \
     hipLaunchKernelGGL((tq::tq_decode_segments_kernel<B, M>), blocks, threads, 0, st, args, N, weighted, scale, \
-                       d, d_pad, seg_off, (uint32_t)nseg, pbytes, out, up)
+                       d, d_pad, seg_off, (uint32_t)nseg, hints, pbytes, out, up)
 #define TQ_LAUNCH_DSEG_M(B) \
     if (accumulate) TQ_LAUNCH_DSEG(B, tq::kAccumulate); else TQ_LAUNCH_DSEG(B, tq::kStore)
     switch (bits) {

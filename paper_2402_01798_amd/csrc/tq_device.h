@@ -100,6 +100,51 @@ __device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ se
     return lo;
 }
 
+// Hints that shorten the search: the tensor in kSegHintBlocks blocks of 2^shift elements (a
+// power of two of at least one tile, so a tile lies in one block) and, per block, the segment
+// that holds its first element.  Built on the host from the caller's host copy of the table;
+// without one, a single block that spans the tensor (the search is then the full one).  The
+// hints only narrow the range: every read stays inside [0, nseg) whatever they hold.
+constexpr int kSegHintBlocks = 256;
+struct SegHints {
+    uint32_t shift;
+    uint32_t first[kSegHintBlocks + 1];
+};
+
+inline SegHints make_seg_hints(const uint64_t* seg_host, uint64_t nseg, uint64_t d)
+{
+    SegHints h;
+    h.shift = 63;
+    for (int j = 0; j <= kSegHintBlocks; ++j) h.first[j] = j == 0 ? 0u : (uint32_t)(nseg - 1);
+    if (!seg_host || nseg < 2) return h;
+    uint32_t shift = 11;                                            // 2048 elements: one tile
+    while (((uint64_t)kSegHintBlocks << shift) < d) ++shift;
+    h.shift = shift;
+    uint64_t s = 0;                                                 // the table ascends: one sweep
+    for (int j = 0; j <= kSegHintBlocks; ++j) {
+        const uint64_t pos = (uint64_t)j << shift;
+        while (s + 1 < nseg && seg_host[s + 1] <= pos) ++s;
+        h.first[j] = (uint32_t)s;
+    }
+    return h;
+}
+
+__device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ seg_off, uint32_t nseg, uint64_t pos,
+                                                 const SegHints& hints)
+{
+    uint64_t j = pos >> hints.shift;
+    j = j < (uint64_t)(kSegHintBlocks - 1) ? j : (uint64_t)(kSegHintBlocks - 1);
+    uint32_t lo = hints.first[j], hi = hints.first[j + 1] + 1u;
+    lo = lo < nseg ? lo : nseg - 1;
+    hi = hi < nseg ? hi : nseg;
+    hi = hi > lo ? hi : lo + 1;
+    while (hi - lo > 1) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if (seg_off[mid] <= pos) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
 // Tile geometry shared by compress and decode.  Workgroup `blk` owns elements
 // [ebase, ebase + kTile) of bucket `bucket`, cut at `eend` (the bucket's end, the last
 // bucket's end being d rounded up to a multiple of 128 so the payload padding is covered).

@@ -602,62 +602,80 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_balanced_reduce_kernel(
 
 // ---- variable-size segments (Sec. V: the layers of a network are quantized independently) ----
 //
-// The tensor is cut at seg_off[0] = 0 < ... < seg_off[nseg] = d (interior offsets multiples of
-// 128) and there is one record per segment.  Work is cut independently of the segments, into
-// chunks of kSegChunk (2^19) elements, one workgroup each, so that the launch depends on d alone: a
-// workgroup takes the pieces of the segments that overlap its chunk one after the other and
-// writes one partial row per piece.  Pieces follow each other along the tensor, and from one
-// piece to the next either the chunk or the segment (or both) advances, so chunk + segment is
-// a unique row number below n_chunks + nseg.  A second kernel adds each segment's rows.
-
-constexpr uint64_t kSegChunk = 1ull << 19;             // elements per workgroup (128 tiles of 4096)
+// Every tensor of the batch is cut at seg_off[0] = 0 < ... < seg_off[nseg] = d (interior offsets
+// multiples of 128) and there is one record per tensor and segment.  Work is cut as for large
+// buckets: the batch in equal shares of tiles, one workgroup each, whatever the segments are.
+// A workgroup takes the pieces of the segments that overlap its share one after the other and
+// writes one partial row per piece, numbered share + global segment index (from one piece to
+// the next one of the two advances: the number is unique and a segment's rows are
+// consecutive); a second kernel adds each segment's rows.  Every access is bounded by d, nseg
+// and the number of rows, whatever the table holds.
 
 template <int DTYPE, bool TAIL>
 __global__ __launch_bounds__(kStatsBlock) void tq_stats_segments_partial_kernel(
-    const void* __restrict__ g, uint64_t d, const uint64_t* __restrict__ seg_off, uint32_t nseg, float g_min,
+    const PtrTable g_tab, uint64_t d, uint64_t tiles_per_tensor, uint64_t total_tiles,
+    const uint64_t* __restrict__ seg_off, uint32_t nseg, float g_min,
     uint32_t* __restrict__ ws_hist, StatsExtra* __restrict__ ws_extra)
 {
-    const uint32_t chunk = linear_block();
-    const uint64_t cstart = (uint64_t)chunk * kSegChunk;
-    if (cstart >= d) return;                                           // padding of a folded grid
-    const uint64_t cend = cstart + kSegChunk < d ? cstart + kSegChunk : d;
+    const uint32_t w = blockIdx.x;
+    uint64_t tile = share_start(w, total_tiles, gridDim.x);
+    const uint64_t tile_end = share_start((uint64_t)w + 1, total_tiles, gridDim.x);
     __shared__ StatsLds L;
-    uint32_t s = find_segment(seg_off, nseg, cstart);
-    for (;;) {
-        // the last segment ends at d whatever the table says: the loop ends with the chunk
-        uint64_t seg_lo = seg_off[s], seg_hi = s + 1 < nseg ? seg_off[s + 1] : d;
-        seg_lo = seg_lo > cstart ? (seg_lo < cend ? seg_lo : cend) : cstart;
-        seg_hi = seg_hi < cend ? (seg_hi > seg_lo ? seg_hi : seg_lo) : cend;
-        seg_lo &= ~7ull;                                               // groups of 8 never straddle a segment
-        const uint64_t r = (uint64_t)chunk + s;
-        const StatsExtra x = stats_slice<DTYPE, TAIL>(g, seg_lo, seg_hi, g_min, L, ws_hist + r * TQ_NBINS);
-        if (threadIdx.x == 0) ws_extra[r] = x;
-        if (seg_hi >= cend || s + 1 >= nseg) break;
-        ++s;
-        __syncthreads();                                               // the histograms are cleared again
+    bool first = true;
+    while (tile < tile_end) {                                          // one pass per tensor the share touches
+        const uint64_t t = tile / tiles_per_tensor, i = tile - t * tiles_per_tensor;
+        const uint64_t i_end = i + (tile_end - tile) < tiles_per_tensor ? i + (tile_end - tile) : tiles_per_tensor;
+        const uint64_t cstart = i * kStatsTile;
+        const uint64_t cend = i_end * kStatsTile < d ? i_end * kStatsTile : d;
+        const void* __restrict__ g = g_tab.p[t];
+        uint32_t s = find_segment(seg_off, nseg, cstart);
+        for (;;) {
+            // the last segment ends at d whatever the table says: the loop ends with the share
+            uint64_t seg_lo = seg_off[s], seg_hi = s + 1 < nseg ? seg_off[s + 1] : d;
+            seg_lo = seg_lo > cstart ? (seg_lo < cend ? seg_lo : cend) : cstart;
+            seg_hi = seg_hi < cend ? (seg_hi > seg_lo ? seg_hi : seg_lo) : cend;
+            seg_lo &= ~7ull;                                           // groups of 8 never straddle a segment
+            const uint64_t r = (uint64_t)w + t * nseg + s;
+            if (!first) __syncthreads();                               // the histograms are cleared again
+            first = false;
+            const StatsExtra x = stats_slice<DTYPE, TAIL>(g, seg_lo, seg_hi, g_min, L, ws_hist + r * TQ_NBINS);
+            if (threadIdx.x == 0) ws_extra[r] = x;
+            if (seg_hi >= cend || s + 1 >= nseg) break;
+            ++s;
+        }
+        tile += i_end - i;
     }
 }
 
-// One workgroup per segment adds the rows of the chunks the segment overlaps.
+// One workgroup per tensor and segment adds the rows of the shares the segment reaches into.
 __global__ __launch_bounds__(kStatsBlock) void tq_stats_segments_reduce_kernel(
-    uint64_t d, const uint64_t* __restrict__ seg_off, uint32_t nseg, float g_min,
+    uint64_t d, uint64_t tiles_per_tensor, uint64_t total_tiles, uint32_t groups, uint32_t count,
+    const uint64_t* __restrict__ seg_off, uint32_t nseg, float g_min,
     const uint32_t* __restrict__ ws_hist, const StatsExtra* __restrict__ ws_extra, uint64_t n_rows,
-    tq_stats_t* __restrict__ stats)
+    const MutPtrTable stats_tab)
 {
-    const uint32_t s = linear_block();
-    if (s >= nseg) return;
+    const uint32_t unit = linear_block();
+    const uint32_t t = unit / nseg, s = unit - t * nseg;
+    if (t >= count) return;                                            // padding of a folded grid
     const uint64_t lo = seg_off[s] < d ? seg_off[s] : d;
     uint64_t hi = s + 1 < nseg ? seg_off[s + 1] : d;
     hi = hi < d ? hi : d;
-    tq_stats_t* S = stats + s;
-    uint64_t r0 = lo / kSegChunk + s, r1 = hi > lo ? (hi - 1) / kSegChunk + s : r0;   // first and last row
-    r1 = r1 < n_rows ? r1 : n_rows - 1;
-    r0 = r0 < r1 ? r0 : r1;
+    tq_stats_t* S = static_cast<tq_stats_t*>(stats_tab.p[t]) + s;
     const bool empty = hi <= lo;                                       // only with a malformed table
+    uint64_t r0 = 0, r1 = 0;                                           // first and last row
+    if (!empty) {
+        const uint64_t base = (uint64_t)t * nseg + s;
+        r0 = share_of_tile((uint64_t)t * tiles_per_tensor + lo / kStatsTile, total_tiles, groups) + base;
+        r1 = share_of_tile((uint64_t)t * tiles_per_tensor + (hi - 1) / kStatsTile, total_tiles, groups) + base;
+        r1 = r1 < n_rows ? r1 : n_rows - 1;
+        r0 = r0 < r1 ? r0 : r1;
+    }
     for (int b = threadIdx.x; b < TQ_NBINS; b += kStatsBlock) {
         uint32_t total = 0u;
-        if (!empty)
+        if (!empty) {
+#pragma unroll 8
             for (uint64_t r = r0; r <= r1; ++r) total += ws_hist[r * TQ_NBINS + b];
+        }
         S->hist[b] = total;
     }
     if (threadIdx.x == 0) {
@@ -859,25 +877,34 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
 uint64_t tq_stats_segments_workspace_bytes_impl(uint64_t d, uint64_t nseg)
 {
     if (d == 0 || nseg == 0) return 0;
-    const uint64_t rows = (d + tq::kSegChunk - 1) / tq::kSegChunk + nseg;
+    // one row per share and per segment; a batch of `count` tensors has count times this much
+    const uint64_t rows = tq::kStatsResidentGroups + nseg;
     return (rows * (TQ_NBINS * 4 + sizeof(tq::StatsExtra)) + 255) / 256 * 256;
 }
 
-// Host side of tq_stats_segments after the argument checks of the C entry point.
-hipError_t tq_launch_stats_segments(const void* g, int dtype, uint64_t d, const uint64_t* seg_off, uint64_t nseg,
-                                    float g_min, tq_stats_t* stats, void* workspace, hipStream_t st)
+// Host side of tq_stats_segments / tq_stats_segments_multi after the argument checks of the C
+// entry points: `count` same-shaped tensors with one segment table in one pair of launches.
+hipError_t tq_launch_stats_segments(const void* const* g, int count, int dtype, uint64_t d, const uint64_t* seg_off,
+                                    uint64_t nseg, float g_min, tq_stats_t* const* stats, void* workspace,
+                                    hipStream_t st)
 {
-    const uint64_t n_chunks = (d + tq::kSegChunk - 1) / tq::kSegChunk;
-    const uint64_t rows = n_chunks + nseg;
+    if (count < 1 || count > tq::kMaxBatch || nseg > 0xFFFFFFFFull) return hipErrorInvalidValue;
+    tq::PtrTable gt{};
+    tq::MutPtrTable stt{};
+    for (int i = 0; i < count; ++i) { gt.p[i] = g[i]; stt.p[i] = stats[i]; }
+    const uint64_t resident = dtype == TQ_BF16 ? tq::kStatsResidentGroups : tq::kStatsTargetGroups;
+    const uint64_t tiles_per_tensor = (d + tq::kStatsTile - 1) / tq::kStatsTile;
+    const uint64_t total_tiles = tiles_per_tensor * (uint64_t)count;
+    const uint64_t fit = total_tiles * tq::kStatsTile / tq::kStatsMinSlice;       // shares of at least 16384 elements
+    const uint32_t groups = (uint32_t)(fit < 1 ? 1 : (fit < resident ? fit : resident));
+    const uint64_t rows = groups + nseg * (uint64_t)count;
     uint32_t* ws_hist = static_cast<uint32_t*>(workspace);
     tq::StatsExtra* ws_extra = reinterpret_cast<tq::StatsExtra*>(static_cast<char*>(workspace) + rows * TQ_NBINS * 4);
-    dim3 pgrid, rgrid;
-    if (nseg > 0xFFFFFFFFull || !tq::fold_grid(n_chunks, tq::kStatsBlock, 1, pgrid) ||
-        !tq::fold_grid(nseg, tq::kStatsBlock, 1, rgrid))
-        return hipErrorInvalidValue;
-#define TQ_LAUNCH_SEG_PARTIAL(DT, TL)                                                                          \
-    hipLaunchKernelGGL((tq::tq_stats_segments_partial_kernel<DT, TL>), pgrid, dim3(tq::kStatsBlock), 0, st, g, d, \
-                       seg_off, (uint32_t)nseg, g_min, ws_hist, ws_extra)
+    dim3 rgrid;
+    if (!tq::fold_grid(nseg * (uint64_t)count, tq::kStatsBlock, 1, rgrid)) return hipErrorInvalidValue;
+#define TQ_LAUNCH_SEG_PARTIAL(DT, TL)                                                                              \
+    hipLaunchKernelGGL((tq::tq_stats_segments_partial_kernel<DT, TL>), dim3(groups), dim3(tq::kStatsBlock), 0, st, gt, \
+                       d, tiles_per_tensor, total_tiles, seg_off, (uint32_t)nseg, g_min, ws_hist, ws_extra)
     if (dtype == TQ_F32) {
         if (g_min > 0.0f) TQ_LAUNCH_SEG_PARTIAL(TQ_F32, true); else TQ_LAUNCH_SEG_PARTIAL(TQ_F32, false);
     } else {
@@ -886,7 +913,7 @@ hipError_t tq_launch_stats_segments(const void* g, int dtype, uint64_t d, const 
 #undef TQ_LAUNCH_SEG_PARTIAL
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(tq::tq_stats_segments_reduce_kernel, rgrid, dim3(tq::kStatsBlock), 0, st, d, seg_off,
-                       (uint32_t)nseg, g_min, ws_hist, ws_extra, rows, stats);
+    hipLaunchKernelGGL(tq::tq_stats_segments_reduce_kernel, rgrid, dim3(tq::kStatsBlock), 0, st, d, tiles_per_tensor,
+                       total_tiles, groups, (uint32_t)count, seg_off, (uint32_t)nseg, g_min, ws_hist, ws_extra, rows, stt);
     return hipGetLastError();
 }

@@ -32,6 +32,7 @@ def test_every_declared_symbol_is_exported(L):
                           "tq_quantize_dequantize", "tq_strerror",
                           "tq_stats_multi", "tq_params_multi", "tq_compress_multi",
                           "tq_stats_segments_workspace_bytes", "tq_stats_segments", "tq_compress_segments",
+                          "tq_stats_segments_multi", "tq_compress_segments_multi",
                           "tq_decompress_aggregate_segments"}
     for n in names:
         assert getattr(L, n) is not None

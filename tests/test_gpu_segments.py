@@ -29,6 +29,29 @@ def run_segments(gs_dev, seg, bits, grid, g_min, seed, step):
     return stats, params, pays, out
 
 
+def run_segments_batched(gs_dev, seg, bits, grid, g_min, seed, step):
+    """The same through the batched entry points: one launch per stage for all workers."""
+    N, d = len(gs_dev), gs_dev[0].numel()
+    stats = [torch.full((seg.nseg * B.STATS_BYTES,), 0x5A, dtype=torch.uint8, device="cuda") for _ in range(N)]
+    ws = torch.full((N * B.stats_segments_workspace_bytes(d, seg.nseg),), 0xC3, dtype=torch.uint8, device="cuda")
+    params = [torch.empty(seg.nseg * B.PARAMS_BYTES, dtype=torch.uint8, device="cuda") for _ in range(N)]
+    pays = [B.alloc_payload(d, bits).fill_(0xA5) for _ in range(N)]
+    out = torch.full((d,), float("nan"), dtype=torch.float32, device="cuda")
+    B.tq_stats_segments_multi(gs_dev, seg, stats, ws, g_min)
+    B.tq_params_multi(stats, params, bits, grid)
+    B.tq_compress_segments_multi(gs_dev, seg, params, pays, bits, seed, 0, step)
+    B.tq_decompress_aggregate_segments(pays, params, seg, out, bits)
+    torch.cuda.synchronize()
+    return stats, params, pays, out
+
+
+def assert_same_bytes(a, b):
+    for xs, ys in zip(a[:3], b[:3]):
+        for x, y in zip(xs, ys):
+            assert torch.equal(x, y)
+    assert torch.equal(a[3], b[3])
+
+
 def check_against_oracle(gs_np, seg, bits, grid, g_min, device, seed, step):
     stats, params, pays, out = device
     d = gs_np[0].size
@@ -66,6 +89,8 @@ def test_ragged_segments_match_oracle(wl, g_min, bits, grid):
     gs = [small_gradient(wl, i, seg.d) for i in range(N)]
     device = run_segments([g[0] for g in gs], seg, bits, grid, g_min, seed=77, step=2)
     check_against_oracle([g[1] for g in gs], seg, bits, grid, g_min, device, 77, 2)
+    # one launch per stage for the three workers: the same bytes
+    assert_same_bytes(device, run_segments_batched([g[0] for g in gs], seg, bits, grid, g_min, seed=77, step=2))
 
 
 def test_layers_of_config_4_as_segments():
