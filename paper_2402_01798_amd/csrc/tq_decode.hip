@@ -196,10 +196,17 @@ __device__ __forceinline__ void fill_level_rows(float* table, const DecodeArgs& 
 // exactly one: the code words of all T tiles are requested first; meanwhile each wavefront
 // fetches the level rows of "its" workers through a scalar (wave-uniform) pointer, expands
 // them to pair entries with two cross-lane reads and writes them to LDS; one barrier.
-template <int BITS, int U, int T, int MODE>
+//
+// SEG: the records are those of variable-size segments instead of buckets.  A workgroup takes
+// T tiles wherever they fall; its reads are requested before the segment is looked up, and
+// when its whole range lies inside one segment (nearly always) the rest is the bucketed code
+// with that segment's record.  Otherwise it takes its tiles one by one, the segments that
+// overlap a tile one after the other, with plain level rows -- the same sums in the same order.
+template <int BITS, int U, int T, int MODE, bool SEG>
 __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     const DecodeArgs args, int N, int weighted, float scale, uint64_t d, uint64_t d_pad, uint64_t bucket_elems,
-    uint32_t groups_per_bucket, uint64_t payload_bytes, float* __restrict__ out, const Update up)
+    uint32_t groups_per_bucket, uint64_t payload_bytes, float* __restrict__ out, const Update up,
+    const uint64_t* __restrict__ seg_off, uint32_t nseg, const SegHints hints)
 {
     constexpr int PAIRS = 1 << (2 * BITS);
     constexpr uint32_t PMASK = PAIRS - 1;
@@ -208,12 +215,19 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
     __shared__ float4 xbuf[kBlock / 64][128];                  // store8_wave's exchange buffers
 
     const uint32_t blk = linear_block();
-    const uint32_t bucket = blk / groups_per_bucket;
-    const uint32_t grp = blk - bucket * groups_per_bucket;
-    const uint64_t bstart = (uint64_t)bucket * bucket_elems;
-    uint64_t bend = bstart + bucket_elems < d_pad ? bstart + bucket_elems : d_pad;
-    bend = bend < d ? bend : d;
-    const uint64_t gstart = bstart + (uint64_t)grp * T * kTile;
+    uint32_t bucket = 0;                                       // the record of the workgroup's range
+    uint64_t gstart, bend;                                     // its first element, the end of what it may take
+    if constexpr (!SEG) {
+        bucket = blk / groups_per_bucket;
+        const uint32_t grp = blk - bucket * groups_per_bucket;
+        const uint64_t bstart = (uint64_t)bucket * bucket_elems;
+        bend = bstart + bucket_elems < d_pad ? bstart + bucket_elems : d_pad;
+        bend = bend < d ? bend : d;
+        gstart = bstart + (uint64_t)grp * T * kTile;
+    } else {
+        gstart = (uint64_t)blk * T * kTile;
+        bend = d;                                              // for the reads; the segment's end comes later
+    }
     if (gstart >= bend) return;
 
     // this lane's group in each tile; lanes past the end read group 0 (always present)
@@ -241,6 +255,53 @@ __global__ __launch_bounds__(kBlock) void tq_decode_fast_kernel(
         if (e0[t] + kGroup <= bend) {
             if constexpr (MODE != kStore && MODE != kStoreStream) load8(out + e0[t], prev[t]);
             if constexpr (MODE == kSgdMomentum) load8(up.velocity + e0[t], vel[t]);
+        }
+    }
+
+    if constexpr (SEG) {
+        __shared__ float rows[16 * 16];                        // plain level rows: U <= 16 workers
+        constexpr uint32_t MASK = (1u << BITS) - 1u;
+        const uint32_t s0 = find_segment(seg_off, nseg, gstart, hints);
+        const uint64_t lo0 = seg_off[s0];
+        const uint64_t hi0 = s0 + 1 < nseg ? seg_off[s0 + 1] : d_pad;
+        if (lo0 <= gstart && gstart + (uint64_t)T * kTile <= (hi0 < d ? hi0 : d)) {
+            bucket = s0;                                       // one record for the whole range: as for a bucket
+        } else {
+            for (int t = 0; t < T; ++t) {                      // the same for the whole workgroup
+                const uint64_t tbase = gstart + (uint64_t)t * kTile;
+                if (tbase >= d) break;
+                const uint64_t tile_end = tbase + kTile < d_pad ? tbase + kTile : d_pad;
+                uint32_t s = t == 0 ? s0 : find_segment(seg_off, nseg, tbase, hints);
+                for (;;) {
+                    const uint64_t seg_lo = seg_off[s];
+                    const uint64_t seg_hi = s + 1 < nseg ? seg_off[s + 1] : d_pad;
+                    __syncthreads();                           // the rows of the segment before are done with
+                    fill_level_rows(rows, args, N, weighted, s);
+                    __syncthreads();
+                    if (e0[t] >= seg_lo && e0[t] < seg_hi && e0[t] < d) {
+                        float acc[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            if (u < N) {
+                                const uint32_t codes = w[t][u] >> cl[t].first_bit;
+#pragma unroll
+                                for (int j = 0; j < 8; ++j) acc[j] = acc[j] + rows[u * 16 + ((codes >> (j * BITS)) & MASK)];
+                            }
+                        }
+                        if (!weighted) {
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) acc[j] = acc[j] * scale;
+                        }
+                        if (e0[t] + kGroup <= d) finish_group<MODE>(out + e0[t], e0[t], acc, prev[t], vel[t], up);
+                        else finish_ragged<MODE>(out + e0[t], e0[t], acc, (int)(d - e0[t]), up);
+                    }
+                    if (seg_hi >= tile_end || s + 1 >= nseg) break;
+                    ++s;
+                }
+            }
+            return;
         }
     }
 
@@ -429,9 +490,11 @@ hipError_t launch_mode(const DecodeGeom& g, float* out, const tq::Update& up, hi
         const uint64_t nblocks = g.nb * gpb;
         dim3 blocks;
         if (!tq::fold_grid(nblocks, tq::kBlock, 1, blocks)) return hipErrorInvalidValue;
+        const tq::SegHints no_hints{};
 #define TQ_LAUNCH_FAST(B, UU, TT)                                                                            \
-    hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, TT, MODE>), blocks, threads, 0, st, g.args, N,      \
-                       g.weighted, g.scale, g.d, g.d_pad, g.be, (uint32_t)gpb, g.pbytes, out, up)
+    hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, TT, MODE, false>), blocks, threads, 0, st, g.args, N, \
+                       g.weighted, g.scale, g.d, g.d_pad, g.be, (uint32_t)gpb, g.pbytes, out, up,               \
+                       static_cast<const uint64_t*>(nullptr), 0u, no_hints)
 #define TQ_LAUNCH_FAST_U(B)                                          \
     switch (U) {                                                     \
         case 1: TQ_LAUNCH_FAST(B, 1, T); break;                      \
@@ -534,6 +597,43 @@ hipError_t tq_launch_decode_segments(const void* const* payload, const tq_params
     const float scale = 1.0f / (float)N;
     const int weighted = weights ? 1 : 0;
     const dim3 threads(tq::kBlock);
+    if (N <= 16 && !(bits == 4 && N > 8)) {
+        // the bucketed kernel's code with the segments' records: two tiles per workgroup wherever they fall
+        constexpr int T = 2;
+        const int U = N <= 1 ? 1 : (N <= 2 ? 2 : (N <= 4 ? 4 : (N <= 8 ? 8 : 16)));
+        dim3 fblocks;
+        if (!tq::fold_grid((d + (uint64_t)T * tq::kTile - 1) / ((uint64_t)T * tq::kTile), tq::kBlock, 1, fblocks))
+            return hipErrorInvalidValue;
+#define TQ_LAUNCH_FSEG(B, UU, M)                                                                                  \
+    hipLaunchKernelGGL((tq::tq_decode_fast_kernel<B, UU, T, M, true>), fblocks, threads, 0, st, args, N, weighted, \
+                       scale, d, d_pad, (uint64_t)0, 0u, pbytes, out, up, seg_off, (uint32_t)nseg, hints)
+#define TQ_LAUNCH_FSEG_M(B, UU) \
+    if (accumulate) TQ_LAUNCH_FSEG(B, UU, tq::kAccumulate); else TQ_LAUNCH_FSEG(B, UU, tq::kStore)
+#define TQ_LAUNCH_FSEG_U(B)                          \
+    switch (U) {                                     \
+        case 1: TQ_LAUNCH_FSEG_M(B, 1); break;       \
+        case 2: TQ_LAUNCH_FSEG_M(B, 2); break;       \
+        case 4: TQ_LAUNCH_FSEG_M(B, 4); break;       \
+        case 8: TQ_LAUNCH_FSEG_M(B, 8); break;       \
+        default: TQ_LAUNCH_FSEG_M(B, 16); break;     \
+    }
+        switch (bits) {
+            case 2: TQ_LAUNCH_FSEG_U(2) break;
+            case 3: TQ_LAUNCH_FSEG_U(3) break;
+            default:
+                switch (U) {
+                    case 1: TQ_LAUNCH_FSEG_M(4, 1); break;
+                    case 2: TQ_LAUNCH_FSEG_M(4, 2); break;
+                    case 4: TQ_LAUNCH_FSEG_M(4, 4); break;
+                    default: TQ_LAUNCH_FSEG_M(4, 8); break;
+                }
+                break;
+        }
+#undef TQ_LAUNCH_FSEG_U
+#undef TQ_LAUNCH_FSEG_M
+#undef TQ_LAUNCH_FSEG
+        return hipGetLastError();
+    }
 #define TQ_LAUNCH_DSEG(B, M)                                                                                   \
     hipLaunchKernelGGL((tq::tq_decode_segments_kernel<B, M>), blocks, threads, 0, st, args, N, weighted, scale, \
                        d, d_pad, seg_off, (uint32_t)nseg, hints, pbytes, out, up)

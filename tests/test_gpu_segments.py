@@ -151,3 +151,14 @@ def test_a_malformed_host_table_is_refused():
         with pytest.raises(B.TqError) as e:
             B.tq_stats_segments(g, seg, st, ws)
         assert e.value.code == B.EINVAL
+
+
+def test_more_workers_than_the_fast_decode_takes():
+    """17 workers: the aggregate goes through the general segment kernel (plain level rows for up to
+    64 workers) instead of the two-tiles-per-workgroup one."""
+    offs = [0, 384, 2048, 2048 + 4096 * 3, 19_968, 19_968 + 128 * 9, 33_001]
+    seg = B.Segments(offs)
+    N, bits = 17, 3
+    gs = [small_gradient("cfg3", i, seg.d) for i in range(N)]
+    device = run_segments_batched([g[0] for g in gs], seg, bits, B.GRID_NONUNIFORM, 1e-5, seed=11, step=4)
+    check_against_oracle([g[1] for g in gs], seg, bits, B.GRID_NONUNIFORM, 1e-5, device, 11, 4)
