@@ -4,17 +4,19 @@
 // caller-fixed g_min, the two terms of the tail-index estimator of Sec. V,
 //   gamma = 1 + n_tail / sum_j ln(|g_j| / g_min).
 //
-// Two launches (one when every bucket is a single slice: the first kernel then writes the
-// records itself), no atomics on global memory (same-address atomics from many workgroups
-// serialise at about 0.14 us each on this part):
-//   1. tq_stats_partial_kernel: each workgroup reads one contiguous slice of one bucket
-//      once, histograms it into replicated LDS histograms (heavy-tailed data puts most lanes
-//      into a handful of bins; replicas spread the same-address LDS atomics) and writes its
-//      partial counts to the caller's workspace as one contiguous row: ws[bucket][slice][bin]
+// Two launches (one when the first kernel can write every record itself), no atomics on
+// global memory (same-address atomics from many workgroups serialise at about 0.14 us each on
+// this part):
+//   1. each workgroup reads contiguous pieces of buckets once, histograms a piece into
+//      replicated LDS histograms (heavy-tailed data puts most lanes into a handful of bins;
+//      replicas spread the same-address LDS atomics) and writes the piece's counts either as
+//      the bucket's finished record or to the caller's workspace as one contiguous row
 //      (scattering them bin-major cost ten times their size in partial-line HBM writes).
-//   2. tq_stats_reduce_kernel: a workgroup per (bucket, 64 bins) adds the slices' rows, 16
-//      slices at a time, with coalesced loads; one more workgroup per bucket combines max,
-//      counts and the log-sum.
+//      Buckets of 32768 elements or more: tq_stats_balanced_kernel, the batch cut into equal
+//      shares whatever the buckets are.  Smaller buckets: tq_stats_partial_kernel, a
+//      workgroup per bucket or per slice of one.
+//   2. a second kernel adds the rows of the buckets that were cut, with coalesced loads, and
+//      combines max, counts and the log-sum.
 // Counts are integers and the tail's log-sum travels as exact integer sums, so the result
 // depends neither on scheduling nor on how the tensor was sliced or batched.
 #include <atomic>
@@ -714,15 +716,12 @@ uint32_t max_slices(uint64_t be, uint64_t nb)
     return (uint32_t)(m < 1 ? 1 : m);
 }
 
-// Slices per bucket for a batch of `count` tensors.  Each workgroup pays for clearing and
-// flushing its LDS histograms -- about what reading 16384 elements costs -- so fewer, longer-lived
-// workgroups win as long as the machine is full, and a launch of W workgroups takes
-// ceil(W / resident) times one workgroup's time, `resident` being the workgroups the launch
-// should keep running at the same time.  The slice count minimises that product.  Measured on
-// MI355X: the fp32 kernels are bound by memory and are fastest with one workgroup per CU
-// (8 x 11.2 M: 71 us against 76 with four); the bf16 kernel is bound by instruction issue and
-// needs the four a CU can hold (4 x 10^9 bf16 with tail terms: 1850 us with 256 workgroups,
-// 1520 with 1024).
+// Slices per bucket for a batch of `count` tensors with buckets of fewer than 32768 elements.
+// Each workgroup pays for clearing and flushing its LDS histograms -- about what reading
+// 16384 elements costs -- so fewer, longer-lived workgroups win as long as the machine is full,
+// and a launch of W workgroups takes ceil(W / resident) times one workgroup's time, `resident`
+// being the workgroups the launch should keep running at the same time.  The slice count
+// minimises that product.
 StatsPlan plan_stats(uint64_t d, uint64_t bucket_elems, int count, uint64_t resident)
 {
     StatsPlan p;
@@ -797,7 +796,9 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
 {
     if (count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
     // bf16 elements cost half the bytes but all the instructions: that kernel is bound by issue and
-    // wants every wavefront slot, the fp32 ones are bound by memory and want the fewest flushes
+    // wants every wavefront slot (4 x 10^9 bf16 with tail terms: 1750 us with 256 workgroups, 1600
+    // with 512, 1460-1520 with 1024); the fp32 ones are bound by memory and read fastest with one
+    // workgroup per compute unit (8 x 124 M fp32: 740 us with four per compute unit, 691 with one)
     const uint64_t resident = dtype == TQ_BF16 ? tq::kStatsResidentGroups : tq::kStatsTargetGroups;
     if (uses_shares(d, bucket_elems)) {
         tq::PtrTable gt{};
