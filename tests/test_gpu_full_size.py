@@ -118,3 +118,49 @@ def test_cfg5_full_size(say):
     """Config 5: 4 workers x 10^9 bf16, non-uniform 2-bit, one codebook per tensor: 4 x 10^9
     element-encodes and 10^9 averages, all compared."""
     check_full("cfg5", 2, B.GRID_NONUNIFORM, say, params_workers=4)
+
+
+def test_cfg4_full_size_one_record_per_layer(say):
+    """Config 4 with one record per LAYER of its recipe (about 200 segments from 2^10 to 2^24 elements)
+    through the batched segment calls bench.py times: 8 workers x 124 M fp32, uniform 2-bit.  The oracle's
+    segment functions are scalar; the eight workers are checked on eight host threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    wl = synth.WORKLOADS["cfg4"]
+    N, d, bits, grid = wl.workers, wl.d, 2, B.GRID_UNIFORM
+    seed, step = 0xC0FFEE, 5
+    t0 = time.time()
+    seg = B.Segments(synth.layer_segments(wl, d))
+    gs_dev = [synth.make_gradient(wl, i, "cuda") for i in range(N)]
+    stats = [torch.full((seg.nseg * B.STATS_BYTES,), 0x5A, dtype=torch.uint8, device="cuda") for _ in range(N)]
+    ws = torch.empty(N * B.stats_segments_workspace_bytes(d, seg.nseg), dtype=torch.uint8, device="cuda")
+    params = [torch.empty(seg.nseg * B.PARAMS_BYTES, dtype=torch.uint8, device="cuda") for _ in range(N)]
+    pays = [B.alloc_payload(d, bits).fill_(0xA5) for _ in range(N)]
+    out = torch.full((d,), float("nan"), dtype=torch.float32, device="cuda")
+    B.tq_stats_segments_multi(gs_dev, seg, stats, ws, wl.g_min)
+    B.tq_params_multi(stats, params, bits, grid)
+    B.tq_compress_segments_multi(gs_dev, seg, params, pays, bits, seed, 0, step)
+    B.tq_decompress_aggregate_segments(pays, params, seg, out, bits)
+    torch.cuda.synchronize()
+    say("cfg4 as %d layer segments: device path done at %.0f s" % (seg.nseg, time.time() - t0))
+    gs_np = [synth.as_numpy(g) for g in gs_dev]
+    del gs_dev
+
+    def check_worker(i):
+        S_or = O.stats_segments(gs_np[i], seg.host, g_min=wl.g_min)
+        S_dev = B.stats_to_numpy(stats[i]).view(O.STATS_DTYPE)
+        for f in ("hist", "n_nonfinite", "n", "n_tail", "absmax", "g_min"):
+            assert (S_dev[f] == S_or[f]).all(), (i, f)
+        assert np.allclose(S_dev["sum_log_tail"], S_or["sum_log_tail"], rtol=1e-6, atol=0)
+        Pd = B.params_to_numpy(params[i]).view(O.PARAMS_DTYPE)
+        P_or = OP.tq_params(S_dev, bits, grid)
+        assert np.allclose(Pd["alpha"], P_or["alpha"], rtol=1e-6) and (Pd["flags"] == P_or["flags"]).all()
+        want = O.compress_segments(gs_np[i], seg.host, Pd, seed, i, step)
+        assert (pays[i].cpu().numpy() == want).all(), ("payload of worker", i)
+        return Pd, want
+
+    with ThreadPoolExecutor(max_workers=min(N, THREADS)) as ex:
+        res = list(ex.map(check_worker, range(N)))
+    say("  statistics, parameters and payloads of %d workers equal at %.0f s" % (N, time.time() - t0))
+    want_out = O.decompress_aggregate_segments([r[1] for r in res], [r[0] for r in res], d, seg.host, bits)
+    assert (out.cpu().numpy() == want_out).all()
+    say("  %d averages equal at %.0f s" % (d, time.time() - t0))
