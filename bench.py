@@ -354,6 +354,28 @@ def compress_roofline(path, res):
     return roof
 
 
+# vector-ALU lane-operations per element of the statistics kernel (profiles/valu_instructions.txt)
+STATS_VALU_PER_ELEM = {"f32": 5.3, "f32/tail": 12.3, "bf16/tail": 11.4}
+
+
+def stats_roofline(path, res):
+    """Roofline object of the statistics kernel (the other long kernel of the step: it reads every
+    gradient once, sz bytes per element, and writes a few MB of histograms)."""
+    us = res["stage_us_per_step"]["stats"]
+    sz = path.g[0].element_size()
+    gbps = path.N * path.d * sz / us / 1e3
+    kernel = "tq_stats_segments_partial_kernel" if path.seg is not None else "tq_stats_balanced_kernel"
+    roof = {"kernel": kernel, "bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(gbps / HBM_PEAK_GBPS, 4),
+            "traffic": load_traffic("tq_stats_balanced_kernel", path.wl.name, path.bits, path.grid),
+            "note": "duration of the statistics stage (both its kernels)"}
+    valu = STATS_VALU_PER_ELEM.get(("bf16" if sz == 2 else "f32") + ("/tail" if path.wl.g_min > 0 else ""))
+    if valu:
+        roof["valu_ops_per_elem"] = valu
+        roof["alu_frac"] = round(path.N * path.d * valu / (us * 1e-6) / 1e12 / ALU_PEAK_TLOPS, 4)
+    return roof
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -415,6 +437,7 @@ def main():
         "stage_gbps": res["stage_gbps"],
         "cold": res.get("cold"),
         "roofline": compress_roofline(path, res),
+        "roofline_stats": stats_roofline(path, res),
     }
     if not a.no_cpu_baseline and not a.segments:
         out["cpu_baseline"] = cpu_baseline(path)
@@ -432,6 +455,7 @@ def main():
             torch.cuda.synchronize()
             r = measure(p2, a.other_steps, 3, min(a.other_steps, 10))
             r["roofline"] = compress_roofline(p2, r)
+            r["roofline_stats"] = stats_roofline(p2, r)
             others["%s/b%d/%s" % (name, b, "uniform" if g == 0 else "nonuniform")] = r
             del p2
             torch.cuda.empty_cache()
@@ -441,6 +465,7 @@ def main():
         r = measure(p2, a.other_steps, 3, 0)
         r["roofline"] = compress_roofline(p2, r)
         r["roofline"]["kernel"] = "tq_compress_segments_kernel"
+        r["roofline_stats"] = stats_roofline(p2, r)
         others["cfg4/b2/uniform/layer-segments"] = r
         del p2
         torch.cuda.empty_cache()
