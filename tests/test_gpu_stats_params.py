@@ -123,3 +123,26 @@ def test_cfg1_alpha_is_the_closed_form_value():
     assert float(P["alpha"][0]) == pytest.approx(7.0710678e-4, rel=0.03)   # sampling error of gamma-hat
     assert float(P["gamma_hat"][0]) == pytest.approx(3.0, abs=0.05)
     assert float(P["rho_hat"][0]) == pytest.approx(0.5, abs=1e-3)
+
+
+@pytest.mark.parametrize("wl,d,bucket,count,g_min", [
+    ("cfg4", 1_000_003, 32_768 + 128 * 3, 3, 0.0),      # buckets that are no multiple of a 4096-element tile
+    ("cfg3", 1_000_003, 32_768 + 128 * 3, 2, 1e-5),     # the same with tail terms
+    ("cfg5", 2_500_001, 1 << 20, 4, 1e-6),              # bf16, 1024 shares over 4 tensors, a ragged end
+    ("cfg4", 9_000_000, 32_768, 2, 0.0),                # more buckets (550) than shares: rows added per boundary
+    ("cfg2", 3_000_000, 0, 1, 0.0),                     # one bucket over 183 shares: the wide second kernel
+    ("cfg1", 70_000, 65_536, 5, 1e-4),                  # shares that span tensors of the batch
+])
+def test_large_buckets_cut_into_equal_shares(wl, d, bucket, count, g_min):
+    """Buckets of 32768 elements or more: the batch is cut into equal shares of tiles whatever the buckets
+    are; records inside one share are written directly, the others added from partial rows."""
+    gs = [small_gradient(wl, 10 + i, d) for i in range(count)]
+    stats = [B.alloc_stats(d, bucket).fill_(0x5A) for _ in range(count)]
+    ws = torch.full((count * B.stats_workspace_bytes(d, bucket),), 0xC3, dtype=torch.uint8, device="cuda")
+    B.tq_stats_multi([g[0] for g in gs], stats, ws, bucket, g_min)
+    torch.cuda.synchronize()
+    for i in range(count):
+        assert_stats_equal(B.stats_to_numpy(stats[i]), O.stats(gs[i][1], bucket_elems=bucket, g_min=g_min))
+        # one tensor alone gives the same bytes (another partition of the same work)
+        single = device_stats(gs[i][0], bucket, g_min)
+        assert torch.equal(single, stats[i])
