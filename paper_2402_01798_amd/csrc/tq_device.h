@@ -6,6 +6,7 @@
 #include <stdlib.h>
 
 #include "tq.h"
+#include "tq_layout.h"
 
 namespace tq {
 
@@ -86,63 +87,6 @@ inline bool fold_grid(uint64_t nblocks, unsigned threads, unsigned count, dim3& 
     if (gz > 65535 || gx * gz > 0xFFFFFFFFull) return false;
     grid = dim3((unsigned)gx, count, (unsigned)gz);
     return true;
-}
-
-// Variable-size segments: the largest s in [0, nseg) with seg_off[s] <= pos.  Every step reads
-// inside [0, nseg], whatever the table holds.
-__device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ seg_off, uint32_t nseg, uint64_t pos)
-{
-    uint32_t lo = 0, hi = nseg;
-    while (hi - lo > 1) {
-        const uint32_t mid = lo + ((hi - lo) >> 1);
-        if (seg_off[mid] <= pos) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-// Hints that shorten the search: the tensor in kSegHintBlocks blocks of 2^shift elements (a
-// power of two of at least one tile, so a tile lies in one block) and, per block, the segment
-// that holds its first element.  Built on the host from the caller's host copy of the table;
-// without one, a single block that spans the tensor (the search is then the full one).  The
-// hints only narrow the range: every read stays inside [0, nseg) whatever they hold.
-constexpr int kSegHintBlocks = 256;
-struct SegHints {
-    uint32_t shift;
-    uint32_t first[kSegHintBlocks + 1];
-};
-
-inline SegHints make_seg_hints(const uint64_t* seg_host, uint64_t nseg, uint64_t d)
-{
-    SegHints h;
-    h.shift = 63;
-    for (int j = 0; j <= kSegHintBlocks; ++j) h.first[j] = j == 0 ? 0u : (uint32_t)(nseg - 1);
-    if (!seg_host || nseg < 2) return h;
-    uint32_t shift = 11;                                            // 2048 elements: one tile
-    while (((uint64_t)kSegHintBlocks << shift) < d) ++shift;
-    h.shift = shift;
-    uint64_t s = 0;                                                 // the table ascends: one sweep
-    for (int j = 0; j <= kSegHintBlocks; ++j) {
-        const uint64_t pos = (uint64_t)j << shift;
-        while (s + 1 < nseg && seg_host[s + 1] <= pos) ++s;
-        h.first[j] = (uint32_t)s;
-    }
-    return h;
-}
-
-__device__ __forceinline__ uint32_t find_segment(const uint64_t* __restrict__ seg_off, uint32_t nseg, uint64_t pos,
-                                                 const SegHints& hints)
-{
-    uint64_t j = pos >> hints.shift;
-    j = j < (uint64_t)(kSegHintBlocks - 1) ? j : (uint64_t)(kSegHintBlocks - 1);
-    uint32_t lo = hints.first[j], hi = hints.first[j + 1] + 1u;
-    lo = lo < nseg ? lo : nseg - 1;
-    hi = hi < nseg ? hi : nseg;
-    hi = hi > lo ? hi : lo + 1;
-    while (hi - lo > 1) {
-        const uint32_t mid = lo + ((hi - lo) >> 1);
-        if (seg_off[mid] <= pos) lo = mid; else hi = mid;
-    }
-    return lo;
 }
 
 // Tile geometry shared by compress and decode.  Workgroup `blk` owns elements

@@ -1,5 +1,5 @@
-// Address arithmetic of the packed payload, free of any HIP type so that the very functions
-// the kernels use can also be compiled for the host and checked there over every size.
+// Address arithmetic of the packed payload and the segment look-up, free of any HIP type so that
+// the very functions the kernels use can also be compiled for the host and checked there.
 #pragma once
 
 #include <stdint.h>
@@ -41,6 +41,77 @@ TQ_HD CodeLoad code_load(uint64_t q, int bits, uint64_t payload_bytes)
         c.first_bit = (uint32_t)(off - c.load_off) * 8u;
     }
     return c;
+}
+
+
+// Variable-size segments: the largest s in [0, nseg) with seg_off[s] <= pos.  Every step reads
+// inside [0, nseg], whatever the table holds.
+TQ_HD uint32_t find_segment(const uint64_t* __restrict__ seg_off, uint32_t nseg, uint64_t pos)
+{
+    uint32_t lo = 0, hi = nseg;
+    while (hi - lo > 1) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if (seg_off[mid] <= pos) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Hints that shorten the search: the tensor in kSegHintBlocks blocks of 2^shift elements (a
+// power of two of at least one tile, so a tile lies in one block) and, per block, the segment
+// that holds its first element.  Built on the host from the caller's host copy of the table;
+// without one, a single block that spans the tensor (the search is then the full one).  The
+// hints only narrow the range: every read stays inside [0, nseg) whatever they hold.
+constexpr int kSegHintBlocks = 256;
+struct SegHints {
+    uint32_t shift;
+    uint32_t first[kSegHintBlocks + 1];
+};
+
+inline SegHints make_seg_hints(const uint64_t* seg_host, uint64_t nseg, uint64_t d)
+{
+    SegHints h;
+    h.shift = 63;
+    for (int j = 0; j <= kSegHintBlocks; ++j) h.first[j] = j == 0 ? 0u : (uint32_t)(nseg - 1);
+    if (!seg_host || nseg < 2) return h;
+    uint32_t shift = 11;                                            // 2048 elements: one tile
+    while (((uint64_t)kSegHintBlocks << shift) < d) ++shift;
+    h.shift = shift;
+    uint64_t s = 0;                                                 // the table ascends: one sweep
+    for (int j = 0; j <= kSegHintBlocks; ++j) {
+        const uint64_t pos = (uint64_t)j << shift;
+        while (s + 1 < nseg && seg_host[s + 1] <= pos) ++s;
+        h.first[j] = (uint32_t)s;
+    }
+    return h;
+}
+
+TQ_HD uint32_t find_segment(const uint64_t* __restrict__ seg_off, uint32_t nseg, uint64_t pos,
+                                                 const SegHints& hints)
+{
+    uint64_t j = pos >> hints.shift;
+    j = j < (uint64_t)(kSegHintBlocks - 1) ? j : (uint64_t)(kSegHintBlocks - 1);
+    uint32_t lo = hints.first[j], hi = hints.first[j + 1] + 1u;
+    lo = lo < nseg ? lo : nseg - 1;
+    hi = hi < nseg ? hi : nseg;
+    hi = hi > lo ? hi : lo + 1;
+    while (hi - lo > 1) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if (seg_off[mid] <= pos) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Equal shares of a batch counted in tiles (the statistics kernels): share w of `groups` is the
+// tiles [share_start(w), share_start(w + 1)) of `total_tiles`.
+TQ_HD uint64_t share_start(uint64_t w, uint64_t total_tiles, uint32_t groups)
+{
+    return w * total_tiles / groups;
+}
+
+// The share that holds a tile: the largest w with share_start(w) <= tile.
+TQ_HD uint32_t share_of_tile(uint64_t tile, uint64_t total_tiles, uint32_t groups)
+{
+    return (uint32_t)(((tile + 1) * groups - 1) / total_tiles);
 }
 
 }  // namespace tq

@@ -474,17 +474,6 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
 
 constexpr uint64_t kBalancedMinBucket = 32768;
 
-__host__ __device__ inline uint64_t share_start(uint64_t w, uint64_t total_tiles, uint32_t groups)
-{
-    return w * total_tiles / groups;
-}
-
-// The share that holds a tile: the largest w with share_start(w) <= tile.
-__host__ __device__ inline uint32_t share_of_tile(uint64_t tile, uint64_t total_tiles, uint32_t groups)
-{
-    return (uint32_t)(((tile + 1) * groups - 1) / total_tiles);
-}
-
 template <int DTYPE, bool TAIL>
 __global__ __launch_bounds__(kStatsBlock) void tq_stats_balanced_kernel(
     const PtrTable g_tab, uint64_t d, uint64_t be, uint64_t nb, uint64_t tiles_per_tensor, uint64_t total_tiles,
