@@ -355,7 +355,7 @@ def compress_roofline(path, res):
 
 
 # vector-ALU lane-operations per element of the statistics kernel (profiles/valu_instructions.txt)
-STATS_VALU_PER_ELEM = {"f32": 5.3, "f32/tail": 12.3, "bf16/tail": 11.4}
+STATS_VALU_PER_ELEM = {"f32": 5.3, "f32/tail": 10.9, "bf16/tail": 9.9}
 
 
 def stats_roofline(path, res):

@@ -131,7 +131,7 @@ __device__ __forceinline__ void write_scalars(tq_stats_t* S, const StatsExtra& x
 struct StatsLds {
     uint32_t hist[kStatsReplicas * kStatsStride];
     uint32_t red_u32[2][kStatsBlock / 64];
-    unsigned long long red_u64[3][kStatsBlock / 64];
+    unsigned long long red_u64[4][kStatsBlock / 64];
 };
 
 // One workgroup (kStatsBlock threads) takes the elements [cstart, cend) of one tensor: their
@@ -196,7 +196,12 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
     uint32_t n_tail_wave = 0u;           // tail elements the whole wavefront has seen in the full trips (same in every lane)
     uint32_t n_tail_lane = 0u;           // tail elements this lane has seen where only part of the wavefront runs
     uint32_t not_counted = 0u;           // values this lane put into bin 0 that do not belong there
-    uint32_t exp_acc = 0u;               // sum of BIASED exponents of the tail elements
+    // The tail's sum of exponents is not accumulated per element: a bin of the histogram lies inside
+    // one octave, so the counts give it -- every element of a bin above g_min's bin is a tail element
+    // with that bin's exponent, and the tail elements of g_min's own bin are the rest of the tail
+    // count.  Only the last bin (61440 and up) spans octaves; its rare elements are taken one by one.
+    constexpr uint32_t kTopBits = (uint32_t)(kBinBias + TQ_NBINS - 1) << 19;   // 61440.0f
+    uint32_t exp_top = 0u, cnt_top = 0u; // BIASED exponents and number of the tail elements in the last bin
     unsigned long long log2m_fix = 0ull; // sum of log2(product of 8 mantissas in [1,2)) in 2^-28 fixed point
 
     // Eight magnitudes (one lane's group of consecutive elements) into the lane's running
@@ -219,14 +224,24 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
             return m03 > m47 ? m03 : m47;
         };
         uint32_t m = max8();
-        if (__builtin_amdgcn_ballot_w64(m >= 0x7F800000u) != 0ull) {   // wavefront-uniform, rare
+        if (__builtin_amdgcn_ballot_w64(m >= kTopBits) != 0ull) {      // wavefront-uniform, rare
+            if (__builtin_amdgcn_ballot_w64(m >= 0x7F800000u) != 0ull) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bool finite = a[j] < 0x7F800000u;
-                nonfinite += finite ? 0u : 1u;
-                a[j] = finite ? a[j] : 0u;
+                for (int j = 0; j < 8; ++j) {
+                    const bool finite = a[j] < 0x7F800000u;
+                    nonfinite += finite ? 0u : 1u;
+                    a[j] = finite ? a[j] : 0u;
+                }
+                m = max8();
             }
-            m = max8();
+            if constexpr (TAIL) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const bool top = a[j] >= kTopBits && a[j] > gmin_bits;
+                    exp_top += top ? a[j] >> 23 : 0u;
+                    cnt_top += top ? 1u : 0u;
+                }
+            }
         }
         amax_bits = m > amax_bits ? m : amax_bits;
 #pragma unroll
@@ -242,8 +257,7 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
                 const bool in_tail = a[j] > gmin_bits;
                 if constexpr (ALL_LANES) n_tail_wave += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(in_tail));
                 else n_tail_lane += in_tail ? 1u : 0u;
-                const uint32_t am = in_tail ? a[j] : 0u;              // exponent 0, mantissa 1.0 outside the tail
-                exp_acc += am >> 23;
+                const uint32_t am = in_tail ? a[j] : 0u;              // mantissa 1.0 outside the tail
                 mant[j] = __uint_as_float((am & 0x007FFFFFu) | 0x3F800000u);
             }
             const float prod = ((mant[0] * mant[1]) * (mant[2] * mant[3])) * ((mant[4] * mant[5]) * (mant[6] * mant[7]));
@@ -324,11 +338,20 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
     __syncthreads();
 
     // the slice's counts, every bin (the destination is not pre-cleared)
+    // ... and, from the same counts, the exponents of the tail elements in the bins above g_min's
+    uint32_t gbin = gmin_bits >> 19;                                   // g_min's bin (g_min >= 2^-40: at least 1)
+    gbin = (gbin > (uint32_t)kBinBias ? gbin - (uint32_t)kBinBias : 0u);
+    gbin = gbin < (uint32_t)(TQ_NBINS - 1) ? gbin : (uint32_t)(TQ_NBINS - 1);
+    unsigned long long exp_bins = 0ull, cnt_bins = 0ull;
     for (int b = threadIdx.x; b < TQ_NBINS; b += kStatsBlock) {
         uint32_t total = 0u;
 #pragma unroll
         for (int r = 0; r < kStatsReplicas; ++r) total += hist[r * kStatsStride + b];
         row[b] = total;
+        if (TAIL && (uint32_t)b > gbin && b < TQ_NBINS - 1) {
+            exp_bins += (unsigned long long)((uint32_t)(kBinBias + b) >> 4) * total;
+            cnt_bins += total;
+        }
     }
 
     // max, counts and log-sum of the slice: wavefront reduction, then thread 0 adds the 8 waves
@@ -336,19 +359,27 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
     amax_bits = wave_reduce_max(amax_bits);
     nonfinite = wave_reduce_add(nonfinite);
     const unsigned long long nt = wave_reduce_add((unsigned long long)n_tail_lane) + n_tail_wave;
-    const unsigned long long es = wave_reduce_add((unsigned long long)exp_acc);
+    const unsigned long long es = wave_reduce_add(exp_bins + exp_top);     // exponents counted so far
+    const unsigned long long cs = wave_reduce_add(cnt_bins + cnt_top);     // ... of this many tail elements
     const unsigned long long lf = wave_reduce_add(log2m_fix);
-    if (lane == 0) { L.red_u32[0][wave] = amax_bits; L.red_u32[1][wave] = nonfinite; L.red_u64[0][wave] = nt; L.red_u64[1][wave] = es; L.red_u64[2][wave] = lf; }
+    if (lane == 0) {
+        L.red_u32[0][wave] = amax_bits; L.red_u32[1][wave] = nonfinite;
+        L.red_u64[0][wave] = nt; L.red_u64[1][wave] = es; L.red_u64[2][wave] = lf; L.red_u64[3][wave] = cs;
+    }
     __syncthreads();
     StatsExtra x{0u, 0u, 0ull, 0ll, 0ull};
     if (threadIdx.x == 0) {
+        unsigned long long counted = 0ull;
         for (int w = 0; w < kStatsBlock / 64; ++w) {
             x.absmax_bits = L.red_u32[0][w] > x.absmax_bits ? L.red_u32[0][w] : x.absmax_bits;
             x.n_nonfinite += L.red_u32[1][w];
             x.n_tail += L.red_u64[0][w];
             x.exp_sum += (long long)L.red_u64[1][w];
             x.log2m_fix += L.red_u64[2][w];
+            counted += L.red_u64[3][w];
         }
+        // the tail elements not counted yet are those of g_min's own bin
+        x.exp_sum += (long long)((uint32_t)(kBinBias + gbin) >> 4) * (long long)(x.n_tail - counted);
         x.exp_sum -= 127ll * (long long)x.n_tail;                      // biased -> unbiased exponents
     }
     return x;
@@ -785,8 +816,8 @@ hipError_t tq_launch_stats(const void* const* g, int count, int dtype, uint64_t 
 {
     if (count < 1 || count > tq::kMaxBatch) return hipErrorInvalidValue;
     // bf16 elements cost half the bytes but all the instructions: that kernel is bound by issue and
-    // wants every wavefront slot (4 x 10^9 bf16 with tail terms: 1750 us with 256 workgroups, 1600
-    // with 512, 1460-1520 with 1024); the fp32 ones are bound by memory and read fastest with one
+    // wants every wavefront slot (4 x 10^9 bf16 with tail terms: 1650 us with 256 workgroups, 1440
+    // with 512, 1410 with 1024; waiting for all loads as the fp32 kernel does: 1550-2050); the fp32 ones are bound by memory and read fastest with one
     // workgroup per compute unit (8 x 124 M fp32: 740 us with four per compute unit, 691 with one)
     const uint64_t resident = dtype == TQ_BF16 ? tq::kStatsResidentGroups : tq::kStatsTargetGroups;
     if (uses_shares(d, bucket_elems)) {
