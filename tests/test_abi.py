@@ -98,6 +98,26 @@ def test_bad_arguments_are_rejected_without_a_device(L):
     assert upd(arr, arr, None, 2, 1000, 0, 3, 0.1, 0.9, 0.0, p, odd, None) == B.EALIGN
     bad = (C.c_void_p * 2)(0x1000, 0)
     assert L.tq_decompress_aggregate(bad, arr, None, 2, 1000, 0, 3, 0, p, None) == B.EINVAL    # null payload
+    # the segment calls: the host copy of the table is checked before anything else
+    import numpy as np
+    good = np.array([0, 128, 1000], dtype=np.uint64)
+    gp = good.ctypes.data_as(C.c_void_p)
+    one = (C.c_void_p * 1)(0x1000)
+    assert L.tq_stats_segments_multi(one, 0, 0, 1000, p, gp, 2, 0.0, one, p, 1 << 30, None) == B.EINVAL     # count = 0
+    assert L.tq_stats_segments_multi(one, 65, 0, 1000, p, gp, 2, 0.0, one, p, 1 << 30, None) == B.EUNSUPPORTED
+    assert L.tq_stats_segments_multi(one, 1, 0, 1000, p, gp, 2, 0.0, one, p, 16, None) == B.EINVAL         # workspace too small
+    assert L.tq_stats_segments_multi(one, 1, 0, 1000, None, gp, 2, 0.0, one, p, 1 << 30, None) == B.EINVAL  # no device table
+    bad = np.array([0, 100, 1000], dtype=np.uint64)                                # interior offset not a multiple of 128
+    assert L.tq_stats_segments_multi(one, 1, 0, 1000, p, bad.ctypes.data_as(C.c_void_p), 2, 0.0, one, p, 1 << 30,
+                                     None) == B.EINVAL
+    big = np.array([0, 128, 1 << 32], dtype=np.uint64)                             # 32-bit counts
+    assert L.tq_stats_segments_multi(one, 1, 0, 1 << 32, p, big.ctypes.data_as(C.c_void_p), 2, 0.0, one, p, 1 << 40,
+                                     None) == B.EUNSUPPORTED
+    assert L.tq_compress_segments_multi(one, 0, 0, 1000, p, gp, 2, one, 2, 0, 0, 0, one, None) == B.EINVAL   # count = 0
+    assert L.tq_compress_segments_multi(one, 65, 0, 1000, p, gp, 2, one, 2, 0, 0, 0, one, None) == B.EUNSUPPORTED
+    assert L.tq_compress_segments_multi(one, 1, 0, 1000, p, gp, 2, one, 5, 0, 0, 0, one, None) == B.EINVAL   # bits
+    odd1 = (C.c_void_p * 1)(0x1004)
+    assert L.tq_compress_segments_multi(odd1, 1, 0, 1000, p, gp, 2, one, 2, 0, 0, 0, one, None) == B.EALIGN
     assert L.tq_strerror(B.EALIGN).decode().startswith("device pointer")
 
 
