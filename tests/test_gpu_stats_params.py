@@ -146,3 +146,37 @@ def test_large_buckets_cut_into_equal_shares(wl, d, bucket, count, g_min):
         # one tensor alone gives the same bytes (another partition of the same work)
         single = device_stats(gs[i][0], bucket, g_min)
         assert torch.equal(single, stats[i])
+
+
+@pytest.mark.parametrize("g_min", [2.0 ** -40, 2.0 ** -40 * (1 + 2.0 ** -20), 0.5, 0.53125, 0.531250059604645,
+                                   61439.99609375, 61440.0, 65536.0, 1.0e5, 3.0e38])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tail_terms_for_thresholds_on_and_between_bin_edges(dtype, g_min):
+    """The tail's exponent sum is taken from the histogram (a bin lies inside one octave) and the tail
+    count of g_min's own bin; the last bin (61440 and up) spans octaves and is taken element by element.
+    Thresholds on bin edges, next to them, inside the last bin and above everything; values spread over
+    every octave from 2^-45 to 2^100."""
+    d = 70_000
+    g_dev, g_np = small_gradient("cfg1", 5, d)
+    g_np = g_np.astype(np.float32).copy()
+    rng = np.random.default_rng(17)
+    idx = rng.choice(d, 6000, replace=False)
+    mags = np.exp2(rng.uniform(-45, 100, idx.size)).astype(np.float32)
+    g_np[idx] = mags * rng.choice([-1.0, 1.0], idx.size).astype(np.float32)
+    g_np[idx[:12]] = [61440.0, -61440.0, 61439.99609375, 65536.0, 65535.99609375, 0.5, 0.53125, -0.5, 2.0 ** -40,
+                      np.inf, np.nan, 3.0e38]
+    if dtype == "bf16":                                  # the oracle reads the bit patterns the device sees
+        g_t = torch.from_numpy(g_np).to(torch.bfloat16)
+        g_np = g_t.view(torch.int16).numpy().view(np.uint16)
+    else:
+        g_t = torch.from_numpy(g_np)
+    def equal(got, want):
+        # the counts exactly; the log-sum to 1e-6, plus what one group's logarithm can be off by when the
+        # tail is a handful of elements next to the threshold and the sum itself is next to zero
+        for f in ("hist", "n_nonfinite", "n", "n_tail", "absmax", "g_min"):
+            assert (got[f] == want[f]).all(), f
+        assert np.allclose(got["sum_log_tail"], want["sum_log_tail"], rtol=1e-6, atol=4e-7)
+
+    equal(B.stats_to_numpy(device_stats(g_t.cuda(), 0, g_min)), O.stats(g_np, g_min=g_min))
+    # small buckets: the other kernel
+    equal(B.stats_to_numpy(device_stats(g_t.cuda(), 16_384, g_min)), O.stats(g_np, bucket_elems=16_384, g_min=g_min))
