@@ -199,8 +199,8 @@ __device__ __forceinline__ StatsExtra stats_slice(const void* __restrict__ g, ui
     // The tail's sum of exponents is not accumulated per element: a bin of the histogram lies inside
     // one octave, so the counts give it -- every element of a bin above g_min's bin is a tail element
     // with that bin's exponent, and the tail elements of g_min's own bin are the rest of the tail
-    // count.  Only the last bin (61440 and up) spans octaves; its rare elements are taken one by one.
-    constexpr uint32_t kTopBits = (uint32_t)(kBinBias + TQ_NBINS - 1) << 19;   // 61440.0f
+    // count.  Only the last bin (65536 and up) spans octaves; its rare elements are taken one by one.
+    constexpr uint32_t kTopBits = (uint32_t)(kBinBias + TQ_NBINS - 1) << 19;   // 65536.0f
     uint32_t exp_top = 0u, cnt_top = 0u; // BIASED exponents and number of the tail elements in the last bin
     unsigned long long log2m_fix = 0ull; // sum of log2(product of 8 mantissas in [1,2)) in 2^-28 fixed point
 

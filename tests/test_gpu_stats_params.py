@@ -149,11 +149,11 @@ def test_large_buckets_cut_into_equal_shares(wl, d, bucket, count, g_min):
 
 
 @pytest.mark.parametrize("g_min", [2.0 ** -40, 2.0 ** -40 * (1 + 2.0 ** -20), 0.5, 0.53125, 0.531250059604645,
-                                   61439.99609375, 61440.0, 65536.0, 1.0e5, 3.0e38])
+                                   61439.99609375, 61440.0, 65536.0, 65535.99609375, 1.0e5, 3.0e38])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_tail_terms_for_thresholds_on_and_between_bin_edges(dtype, g_min):
     """The tail's exponent sum is taken from the histogram (a bin lies inside one octave) and the tail
-    count of g_min's own bin; the last bin (61440 and up) spans octaves and is taken element by element.
+    count of g_min's own bin; the last bin (65536 and up) spans octaves and is taken element by element.
     Thresholds on bin edges, next to them, inside the last bin and above everything; values spread over
     every octave from 2^-45 to 2^100."""
     d = 70_000
