@@ -500,8 +500,8 @@ __global__ __launch_bounds__(kReduceBlock) void tq_stats_reduce_kernel(
 // finished record; the pieces of the others go to partial rows, numbered share + global bucket
 // index (from one piece to the next one of the two advances, so the number is unique and a
 // bucket's rows are consecutive), and a second kernel adds them.  Every workgroup reads the
-// same number of bytes, so the launch has no partly filled last round: with one bucket per
-// workgroup 8 x 119 buckets of 2^20 on 256 compute units took four rounds for 3.7 rounds' work.
+// same number of bytes, so no compute unit is left idle at the end: with one bucket per
+// workgroup 8 x 119 buckets of 2^20 on 256 compute units took four passes for 3.7 passes of work.
 
 constexpr uint64_t kBalancedMinBucket = 32768;
 
