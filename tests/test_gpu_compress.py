@@ -120,6 +120,38 @@ def test_empty_end_cells_and_values_beyond_the_threshold(lv, dtype):
     assert below.size > 0 and (codes[below] > 0).all()        # truncated onto the repeated level: the cell above
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("log2_width", [-20, -109, -110, -111, -112, -113, -120, 100, 120])
+def test_very_narrow_and_very_wide_cells(log2_width, bits, dtype):
+    """Cells so narrow that their reciprocal width is near the top of the binary32 range, and very wide
+    ones: values spread over the codebook, at and next to every level, far beyond it, +-Inf, NaN; every
+    code equal to the oracle's."""
+    s = (1 << bits) - 1
+    w = np.float64(2.0) ** log2_width
+    lv = ((np.arange(s + 1) - s / 2.0) * w * (1.0 + 0.25 * (np.arange(s + 1) % 3))).astype(np.float32)   # unequal cells
+    lv = np.sort(lv)
+    P = np.zeros(1, dtype=O.PARAMS_DTYPE)
+    P["alpha"], P["bits"], P["s"], P["grid"] = lv[-1], bits, s, O.GRID_NONUNIFORM
+    P["level"][0, : s + 1] = lv
+    width = np.diff(lv.astype(np.float64))
+    with np.errstate(over="ignore"):
+        iw = (1.0 / width).astype(np.float32)
+    P["inv_w"][0, :s] = np.where(np.isfinite(iw), iw, 0.0)            # a reciprocal beyond the range is stored as 0
+    d = 2 * 2048 + 333
+    rng = np.random.default_rng(bits * 1000 + log2_width)
+    g = (rng.uniform(-1.2, 1.2, d) * float(lv[-1])).astype(np.float32)
+    near = np.concatenate([[l, np.nextafter(l, np.float32(np.inf)), np.nextafter(l, np.float32(-np.inf))] for l in lv])
+    special = np.concatenate([near, np.array([0.0, -0.0, 3e38, -3e38, np.inf, -np.inf, np.nan], dtype=np.float32)])
+    g[: special.size] = special
+    g[-special.size:] = special
+    t = torch.from_numpy(g.astype(np.float32)).to(dtype)
+    g_np = t.view(torch.int16).numpy().view("uint16") if dtype == torch.bfloat16 else t.numpy()
+    for seed in (1, 99):
+        got = device_compress(t.cuda(), P, bits, seed, 3, 7).cpu().numpy()
+        assert (got == O.compress(g_np, P, seed, 3, 7)).all()
+
+
 @pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("d", [1, 5, 40, 41, 42, 43, 85, 86, 127, 128, 129, 2049, 4096 + 41])
 def test_nothing_is_written_past_the_payload(bits, d):
